@@ -1,0 +1,282 @@
+"""Seeded synthetic token batches shaped like BatchLLM's workloads.
+
+This module only draws lengths and random values; it holds none of the method's
+arithmetic and is the one piece of code both the CPU oracle's tests and the HIP
+path's tests/benchmark use.  The paper's real inputs (model activations, the
+industry snippet-generation set of Sec. 4.2.2) are not available; these batches
+reproduce their shapes: shared-prefix length / distinct length / requests per
+group (Sec. 4.3.3 kernel benchmark, Sec. 4.2.1 micro-benchmarks).
+
+Random stream (numpy Philox keyed by the seed), drawn in this fixed order:
+  prefix lengths (one per group) -> group sizes -> per-request class
+  (decode / prefill) -> per-request suffix lengths -> optional user-order shuffle.
+Values are i.i.d. N(0,1), rounded to the run's dtype, from a second Philox
+stream keyed by (seed, tensor index).
+"""
+from dataclasses import dataclass, field
+import numpy as np
+
+F32 = 0
+BF16 = 1
+
+
+@dataclass
+class Layer:
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    dtype: int
+
+
+@dataclass
+class Batch:
+    """Lengths of one token batch, in USER request order."""
+    name: str
+    layer: Layer
+    prefix_len: np.ndarray        # [G] int32
+    req_group: np.ndarray         # [R] int32
+    req_suffix_len: np.ndarray    # [R] int32  (s_r, includes this iteration's tokens)
+    req_q_len: np.ndarray         # [R] int32  (0 idle, 1 decode, >1 prefill chunk)
+    seed: int = 0
+    note: str = ""
+
+    @property
+    def n_groups(self):
+        return int(self.prefix_len.shape[0])
+
+    @property
+    def n_requests(self):
+        return int(self.req_group.shape[0])
+
+    @property
+    def n_rows(self):
+        return int(self.req_q_len.sum())
+
+    @property
+    def n_prefix_kv(self):
+        return int(self.prefix_len.sum())
+
+    @property
+    def n_suffix_kv(self):
+        return int(self.req_suffix_len.sum())
+
+
+def _rng(seed, stream=0):
+    return np.random.Generator(np.random.Philox(key=[int(seed), int(stream)]))
+
+
+def _uniform(rng, lo, hi, n):
+    return rng.integers(lo, hi + 1, size=n, dtype=np.int64)
+
+
+def _zipf_sizes(rng, n, s, kmax):
+    k = np.arange(1, kmax + 1, dtype=np.float64)
+    pmf = k ** (-s)
+    pmf /= pmf.sum()
+    return rng.choice(np.arange(1, kmax + 1), size=n, p=pmf)
+
+
+def _finish(name, layer, prefix_len, req_group, s, q, seed, shuffle, rng, note=""):
+    req_group = np.asarray(req_group, dtype=np.int32)
+    s = np.asarray(s, dtype=np.int32)
+    q = np.asarray(q, dtype=np.int32)
+    if shuffle:
+        perm = rng.permutation(len(req_group))
+        req_group, s, q = req_group[perm], s[perm], q[perm]
+    return Batch(name, layer, np.asarray(prefix_len, dtype=np.int32), req_group, s, q,
+                 seed=seed, note=note)
+
+
+def tiny_fp32(seed=0, shuffle=False):
+    """1 group, MHA 4 heads, D=64, prefix 64, 4 requests x (16 suffix KV, 1 decode row)."""
+    rng = _rng(seed)
+    layer = Layer(4, 4, 64, F32)
+    return _finish("tiny_fp32", layer, [64], [0] * 4, [16] * 4, [1] * 4, seed, shuffle, rng)
+
+
+def l8b_decode(seed=0, shuffle=False):
+    """Llama-3-8B-shaped decode: 8 groups x 32 requests, prefix 2048, suffix U[64,512]."""
+    rng = _rng(seed)
+    layer = Layer(32, 8, 128, BF16)
+    g, per = 8, 32
+    prefix_len = np.full(g, 2048)
+    req_group = np.repeat(np.arange(g), per)
+    s = _uniform(rng, 64, 512, g * per)
+    q = np.ones(g * per)
+    return _finish("l8b_decode", layer, prefix_len, req_group, s, q, seed, shuffle, rng)
+
+
+def l8b_mixed(seed=0, shuffle=False, full=False):
+    """16 groups, prefix U[512,4096], 64 requests/group, half decode (suffix U[32,256]).
+
+    The other half are prefill-class requests with 256-token chunks.  "Token batch
+    about 16k" cannot hold all 512 chunks, so by default only the 4 lowest-indexed
+    prefill-class requests of each group contribute a chunk this iteration and the
+    rest are idle (q=0): T = 512 + 64*256 = 16896.  full=True schedules all 512
+    chunks (T = 131584).  Even in-group index = decode, odd = prefill class.
+    A prefill request's suffix is s_prev + 256 with s_prev U{0..256}; an idle
+    request holds s_prev.
+    """
+    rng = _rng(seed)
+    layer = Layer(32, 8, 128, BF16)
+    g, per = 16, 64
+    prefix_len = _uniform(rng, 512, 4096, g)
+    req_group = np.repeat(np.arange(g), per)
+    in_group = np.tile(np.arange(per), g)
+    is_decode = (in_group % 2) == 0
+    s_dec = _uniform(rng, 32, 256, g * per)
+    s_prev = _uniform(rng, 0, 256, g * per)
+    chunk_now = (~is_decode) & ((in_group // 2) < 4 if not full else True)
+    s = np.where(is_decode, s_dec, np.where(chunk_now, s_prev + 256, s_prev))
+    q = np.where(is_decode, 1, np.where(chunk_now, 256, 0))
+    name = "l8b_mixed_full" if full else "l8b_mixed"
+    return _finish(name, layer, prefix_len, req_group, s, q, seed, shuffle, rng)
+
+
+def rank_longprefix(seed=0, shuffle=False):
+    """Search-ranking-shaped: 4 groups x 256 requests, prefix 8192, suffix U[16,128], decode."""
+    rng = _rng(seed)
+    layer = Layer(32, 8, 128, BF16)
+    g, per = 4, 256
+    prefix_len = np.full(g, 8192)
+    req_group = np.repeat(np.arange(g), per)
+    s = _uniform(rng, 16, 128, g * per)
+    q = np.ones(g * per)
+    return _finish("rank_longprefix", layer, prefix_len, req_group, s, q, seed, shuffle, rng)
+
+
+def l70b_zipf(seed=0, shuffle=False, token_budget=None):
+    """Llama-3-70B-shaped: 64/8 heads, 32 groups, Zipf(1.1) sizes in 1..512,
+    prefix U[256,8192], suffix U[32,1024]; each request is a decode row with
+    probability 1/2, else a prefill chunk of min(512, s) rows.  token_budget
+    (e.g. 32768) keeps chunks in request order until the budget is used; later
+    prefill-class requests are idle."""
+    rng = _rng(seed)
+    layer = Layer(64, 8, 128, BF16)
+    g = 32
+    prefix_len = _uniform(rng, 256, 8192, g)
+    sizes = _zipf_sizes(rng, g, 1.1, 512)
+    req_group = np.repeat(np.arange(g), sizes)
+    n = int(sizes.sum())
+    is_decode = rng.integers(0, 2, size=n) == 0
+    s = _uniform(rng, 32, 1024, n)
+    q = np.where(is_decode, 1, np.minimum(512, s))
+    name = "l70b_zipf"
+    if token_budget is not None:
+        used = int(is_decode.sum())
+        for r in range(n):
+            if not is_decode[r]:
+                if used + q[r] <= token_budget:
+                    used += int(q[r])
+                else:
+                    q[r] = 0
+        name = "l70b_zipf_%dk" % (token_budget // 1024)
+    return _finish(name, layer, prefix_len, req_group, s, q, seed, shuffle, rng)
+
+
+def kernel_bench_shape(prefix, distinct, n_decode, n_prefill=0, chunk=256, seed=0,
+                       layer=None, shuffle=False):
+    """One group shaped like the paper's kernel benchmark setting i/j/all (Sec. 4.3.3):
+    shared prefix i, distinct length j per request, all requests in one group;
+    n_prefill requests carry a prefill chunk besides n_decode decode rows."""
+    rng = _rng(seed)
+    layer = layer or Layer(32, 8, 128, BF16)
+    n = n_decode + n_prefill
+    s = np.full(n, distinct)
+    q = np.concatenate([np.ones(n_decode), np.full(n_prefill, min(chunk, distinct))])
+    return _finish("e11_%d_%d_%d+%d" % (prefix, distinct, n_decode, n_prefill), layer,
+                   [prefix], np.zeros(n), s, q, seed, shuffle, rng)
+
+
+def industry_shaped(n_groups=512, seed=0, shuffle=False):
+    """Share degree about 3, prefix about 1570, distinct about 30 (Sec. 4.2.2), decode rows."""
+    rng = _rng(seed)
+    layer = Layer(32, 8, 128, BF16)
+    prefix_len = _uniform(rng, 1570 - 400, 1570 + 400, n_groups)
+    sizes = _uniform(rng, 1, 5, n_groups)
+    req_group = np.repeat(np.arange(n_groups), sizes)
+    n = int(sizes.sum())
+    s = _uniform(rng, 10, 50, n)
+    return _finish("industry_shaped", layer, prefix_len, req_group, s, np.ones(n), seed, shuffle, rng)
+
+
+def ragged_toy(seed=0, dtype=F32, n_q_heads=4, n_kv_heads=2, head_dim=64, shuffle=True,
+               n_groups=3, max_prefix=70, max_group=5, max_suffix=40, max_chunk=24):
+    """Small ragged batch with every degenerate case the method has: an empty
+    prefix, a group of one, idle requests, decode rows, prefill chunks shorter
+    than and equal to the suffix, suffix length 1."""
+    rng = _rng(seed)
+    layer = Layer(n_q_heads, n_kv_heads, head_dim, dtype)
+    prefix_len = _uniform(rng, 0, max_prefix, n_groups)
+    prefix_len[rng.integers(0, n_groups)] = 0
+    sizes = _uniform(rng, 1, max_group, n_groups)
+    sizes[rng.integers(0, n_groups)] = 1
+    req_group = np.repeat(np.arange(n_groups), sizes)
+    n = int(sizes.sum())
+    cls = rng.integers(0, 4, size=n)            # 0 idle, 1 decode, 2 chunk, 3 chunk == whole suffix
+    s = _uniform(rng, 1, max_suffix, n)
+    q = np.zeros(n, dtype=np.int64)
+    for r in range(n):
+        if cls[r] == 1:
+            q[r] = 1
+        elif cls[r] == 2:
+            q[r] = min(int(s[r]), int(rng.integers(2, max_chunk + 1)))
+        elif cls[r] == 3:
+            q[r] = min(int(s[r]), max_chunk)
+            s[r] = q[r]
+    if q.sum() == 0:
+        q[0] = 1
+    return _finish("ragged_toy", layer, prefix_len, req_group, s, q, seed, shuffle, rng)
+
+
+CONFIGS = {
+    "tiny_fp32": tiny_fp32,
+    "l8b_decode": l8b_decode,
+    "l8b_mixed": l8b_mixed,
+    "l8b_mixed_full": lambda seed=0, shuffle=False: l8b_mixed(seed, shuffle, full=True),
+    "rank_longprefix": rank_longprefix,
+    "l70b_zipf": l70b_zipf,
+    "l70b_zipf_32k": lambda seed=0, shuffle=False: l70b_zipf(seed, shuffle, token_budget=32768),
+}
+
+
+# ---------------------------------------------------------------- values ----
+
+def round_to_bf16(x32):
+    """Round float32 to the nearest bfloat16 (ties to even); returns (float32 view of
+    the rounded values, uint16 bit patterns)."""
+    x32 = np.ascontiguousarray(x32, dtype=np.float32)
+    u = x32.view(np.uint32)
+    bias = ((u >> 16) & 1) + np.uint32(0x7FFF)
+    bits = ((u + bias) >> 16).astype(np.uint16)
+    back = (bits.astype(np.uint32) << 16).view(np.float32)
+    return back, bits
+
+
+def bf16_bits_to_f32(bits):
+    return (np.asarray(bits, dtype=np.uint16).astype(np.uint32) << 16).view(np.float32)
+
+
+def draw_values(batch, seed=None):
+    """N(0,1) Q, K, V for a batch, already rounded to the layer's dtype.
+
+    Returns float32 arrays (exactly representable in the dtype):
+      q [T,Hq,D] in USER row order, k_prefix/v_prefix [sum Lp,Hkv,D],
+      k_suffix/v_suffix [sum s,Hkv,D] in user request order.
+    """
+    seed = batch.seed if seed is None else seed
+    L = batch.layer
+    shapes = {
+        "q": (batch.n_rows, L.n_q_heads, L.head_dim),
+        "k_prefix": (batch.n_prefix_kv, L.n_kv_heads, L.head_dim),
+        "v_prefix": (batch.n_prefix_kv, L.n_kv_heads, L.head_dim),
+        "k_suffix": (batch.n_suffix_kv, L.n_kv_heads, L.head_dim),
+        "v_suffix": (batch.n_suffix_kv, L.n_kv_heads, L.head_dim),
+    }
+    out = {}
+    for i, (name, shp) in enumerate(shapes.items()):
+        x = _rng(seed, 100 + i).standard_normal(size=shp, dtype=np.float32)
+        if L.dtype == BF16:
+            x, _ = round_to_bf16(x)
+        out[name] = x
+    return out
