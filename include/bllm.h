@@ -1,0 +1,180 @@
+/*
+ * bllm -- prefix-shared attention for one MI355X (gfx950), C ABI.
+ *
+ * The operation is the attention backend of BatchLLM (Sec. 3.4 "attention
+ * backend", Sec. 4.3.3, Sec. 5): in one token-batch (decode tokens mixed with
+ * prefill chunks, Sec. 3.3.1) every request belongs to a prefix-sharing group;
+ * its query tokens attend to the group's shared prefix KV and to the request's
+ * own distinct (suffix) KV.  The two parts are evaluated separately -- the
+ * prefix part as a matrix-matrix product over all queries of the group -- and
+ * reduced with online softmax.
+ *
+ * Conventions
+ *   - All functions return BLLM_OK (0) or a negative bllm_status; nothing throws
+ *     across this boundary.  bllm_last_error() gives thread-local text for the
+ *     last failure on the calling thread.
+ *   - "host" pointers are ordinary CPU memory; "device" pointers are HIP device
+ *     memory on the device that was current when the handle was created.
+ *   - hip_stream is a hipStream_t passed as void* (NULL = the null stream).
+ *     Device calls only enqueue work on that stream: no synchronisation, no
+ *     allocation.  The caller owns every tensor and the stream.
+ *   - Logical layouts (row-major, innermost last):
+ *       q          [T, Hq, D]        rows in PACKED order (see bllm_packing_view)
+ *       k_prefix   [sum Lp, Hkv, D]  group g at rows prefix_kv_start[g] ...
+ *       k_suffix   [sum s,  Hkv, D]  USER request order, request r at rows
+ *                                    req_kv_start[r] ... (idle requests included)
+ *       o partial  [T, Hq, D] fp32,  lse partial [T, Hq] fp32 (natural log of
+ *                                    sum exp(scale * q.k); -inf for an empty part,
+ *                                    whose output rows are 0)
+ *     Element type of q/k/v and of the merged output is bllm_layer_desc.dtype.
+ *   - Query head h uses KV head h / (Hq / Hkv).
+ *   - A request with suffix length s and q_len rows has its rows at suffix
+ *     positions s-q_len .. s-1; row i sees suffix positions 0 .. s-q_len+i and the
+ *     whole prefix of its group.
+ */
+#ifndef BLLM_H
+#define BLLM_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    BLLM_OK = 0,
+    BLLM_INVALID_ARG = -1,   /* null pointer, negative length, group id out of range, q_len > suffix_len ... */
+    BLLM_UNSUPPORTED = -2,   /* shape / dtype outside what the kernels cover; caller may fall back (Sec. 3.4) */
+    BLLM_OUT_OF_MEMORY = -3,
+    BLLM_HIP_ERROR = -4
+} bllm_status;
+
+enum { BLLM_F32 = 0, BLLM_BF16 = 1 };
+
+typedef struct {
+    int32_t n_q_heads;       /* Hq */
+    int32_t n_kv_heads;      /* Hkv, divides Hq; Hq/Hkv in {1,2,4,8} */
+    int32_t head_dim;        /* D: 64 or 128 */
+    int32_t dtype;           /* BLLM_F32 or BLLM_BF16: type of q, k, v and of the merged output */
+    float   softmax_scale;   /* 0 => 1/sqrt(head_dim) */
+} bllm_layer_desc;
+
+typedef struct bllm_prefix_groups bllm_prefix_groups;   /* opaque, immutable after create */
+
+/* Host views of the packing metadata of a handle (valid until destroy).
+ * Packed order: active requests (q_len > 0) stably sorted by
+ * (group, decode row before prefill chunk, user index); rows of a request
+ * consecutive in suffix-position order. */
+typedef struct {
+    int32_t n_groups, n_requests;
+    int32_t n_rows;                    /* T = sum of q_len */
+    int32_t n_active;                  /* requests with q_len > 0 */
+    const int32_t* perm_req;           /* [n_active]   packed request -> user request */
+    const int32_t* req_row_start;      /* [n_active+1] first packed row of each packed request */
+    const int32_t* group_req_start;    /* [G+1] first packed request of each group */
+    const int32_t* group_row_start;    /* [G+1] first packed row of each group */
+    const int32_t* group_decode_rows;  /* [G]   decode rows of the group (they come first) */
+    const int32_t* prefix_kv_start;    /* [G+1] first prefix KV row of each group */
+    const int32_t* req_kv_start;       /* [R+1] first suffix KV row of each USER request */
+    const int32_t* row_req;            /* [T]   user request of each packed row */
+    const int32_t* row_pos;            /* [T]   suffix position of each packed row */
+    const int32_t* row_src;            /* [T]   index of the row in user row order (gather map for q) */
+    /* Work lists the kernels consume; BLLM_ITEM_INTS int32 per item, fields in
+     * the order of bllm_item_field.  Built by fixed rules from the arrays above
+     * and the tile constants below. */
+    int32_t n_prefix_tile_items;  const int32_t* prefix_tile_items;   /* MFMA tiles of the shared-prefix pass */
+    int32_t n_prefix_row_items;   const int32_t* prefix_row_items;    /* per-row streaming items of the prefix pass (fp32 / fallback) */
+    int32_t n_suffix_tile_items;  const int32_t* suffix_tile_items;   /* MFMA tiles of prefill chunks */
+    int32_t n_suffix_row_items;   const int32_t* suffix_row_items;    /* per-row streaming items (decode rows; all rows for fp32) */
+    int32_t tile_rows;                 /* token rows per MFMA tile (stacked rows / (Hq/Hkv)) */
+    int32_t prefix_split_len;          /* prefix KV rows per split (multiple of 64), 0 = no split */
+    int32_t suffix_split_len;          /* suffix KV rows per streaming split, 0 = no split */
+    int32_t n_prefix_ws_rows;          /* rows of split-partial workspace the prefix pass uses */
+    int32_t n_suffix_ws_rows;          /* same for the suffix pass */
+    const int32_t* prefix_row_split;   /* [T][3] per packed row: workspace row of split 0, stride between splits, number of splits (0 = written directly) */
+    const int32_t* suffix_row_split;   /* [T][3] same for the suffix pass */
+} bllm_packing_view;
+
+#define BLLM_ITEM_INTS 8
+typedef enum {
+    BLLM_ITEM_Q_ROW0 = 0,    /* first packed row */
+    BLLM_ITEM_N_ROWS = 1,    /* token rows covered (1 for a streaming item) */
+    BLLM_ITEM_KV_HEAD = 2,
+    BLLM_ITEM_KV_ROW0 = 3,   /* first KV row (absolute row of the prefix or suffix KV array) */
+    BLLM_ITEM_KV_LEN = 4,    /* KV rows in this item's range */
+    BLLM_ITEM_VIS0 = 5,      /* KV rows of the range visible to the item's first row; row i sees min(KV_LEN, VIS0 + i) */
+    BLLM_ITEM_DST_ROW = 6,   /* >= 0: row of the split workspace for the first row; -1: write the pass output directly */
+    BLLM_ITEM_RESERVED = 7
+} bllm_item_field;
+
+/* Build the packing metadata of one token-batch (Sec. 3.3.1: decode tokens
+ * and prefill chunks of requests organised in prefix-sharing groups; Sec. 3.4:
+ * per-request metadata separating shared prefix from distinct part) and upload
+ * it to the current device.
+ *   desc            host; copied
+ *   prefix_len      host [n_groups]   Lp_g >= 0
+ *   req_group       host [n_requests] in 0 .. n_groups-1
+ *   req_suffix_len  host [n_requests] s_r >= q_r
+ *   req_q_len       host [n_requests] 0 idle, 1 decode, > 1 prefill chunk
+ * Host arrays are copied and may be freed on return.  Allocates the handle's
+ * device metadata and split workspace (the only allocation the library makes)
+ * and synchronises hip_stream once.  *out is set only on success; release with
+ * bllm_prefix_group_destroy.
+ * Errors: INVALID_ARG (bad pointers/lengths, n_groups < 1, overflow of int32
+ * offsets), UNSUPPORTED (head_dim, head ratio, dtype), OUT_OF_MEMORY, HIP_ERROR. */
+int bllm_prefix_group_create(const bllm_layer_desc* desc,
+                             int32_t n_groups, const int32_t* prefix_len,
+                             int32_t n_requests, const int32_t* req_group,
+                             const int32_t* req_suffix_len, const int32_t* req_q_len,
+                             void* hip_stream, bllm_prefix_groups** out);
+
+/* Same packing, host side only: no device is touched, the handle can be
+ * inspected with bllm_prefix_group_metadata but every device call on it returns
+ * BLLM_INVALID_ARG.  For metadata checks on machines without a GPU. */
+int bllm_prefix_group_create_host(const bllm_layer_desc* desc,
+                                  int32_t n_groups, const int32_t* prefix_len,
+                                  int32_t n_requests, const int32_t* req_group,
+                                  const int32_t* req_suffix_len, const int32_t* req_q_len,
+                                  bllm_prefix_groups** out);
+
+int bllm_prefix_group_metadata(const bllm_prefix_groups* pg, bllm_packing_view* out);
+int bllm_prefix_group_destroy(bllm_prefix_groups* pg);
+
+/* Partial attention of every packed row over its group's shared prefix KV
+ * (Sec. 4.3.3, Sec. 5: the part that becomes a matrix-matrix product because
+ * all queries of a group share the keys).  No mask.
+ *   q                  device [T,Hq,D]       packed order, desc.dtype
+ *   k_prefix, v_prefix device [sum Lp,Hkv,D] desc.dtype
+ *   o_part             device [T,Hq,D] fp32  normalised partial output (0 where Lp = 0)
+ *   lse_part           device [T,Hq]   fp32  log-sum-exp (-inf where Lp = 0)
+ * Every element of o_part / lse_part is written. */
+int bllm_shared_prefix_attention(const bllm_prefix_groups* pg, const void* q,
+                                 const void* k_prefix, const void* v_prefix,
+                                 float* o_part, float* lse_part, void* hip_stream);
+
+/* Partial attention of every packed row over its own request's distinct
+ * (suffix) KV, causal inside the suffix (Sec. 4.3.3, Sec. 5: the per-request
+ * part; a decode row is a matrix-vector product).  Arguments as above with
+ * k_suffix, v_suffix device [sum s,Hkv,D] in user request order. */
+int bllm_suffix_attention(const bllm_prefix_groups* pg, const void* q,
+                          const void* k_suffix, const void* v_suffix,
+                          float* o_part, float* lse_part, void* hip_stream);
+
+/* Online-softmax reduction of two partial results over disjoint key sets
+ * (Sec. 5): o = (w_a o_a + w_b o_b)/(w_a + w_b), w_x = exp(lse_x - max),
+ * lse = max + log(w_a + w_b); a part with lse = -inf has weight 0.
+ *   o_a, o_b device [T,Hq,D] fp32; lse_a, lse_b device [T,Hq] fp32
+ *   o_out    device [T,Hq,D] desc.dtype
+ *   lse_out  device [T,Hq] fp32, or NULL */
+int bllm_lse_merge(const bllm_prefix_groups* pg,
+                   const float* o_a, const float* lse_a,
+                   const float* o_b, const float* lse_b,
+                   void* o_out, float* lse_out, void* hip_stream);
+
+const char* bllm_last_error(void);
+const char* bllm_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BLLM_H */

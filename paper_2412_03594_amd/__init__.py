@@ -1,0 +1,13 @@
+"""bllm -- prefix-shared attention for one MI355X (gfx950).
+
+Thin ctypes binding over libbllm.so (C ABI declared in include/bllm.h).  It only
+marshals arguments: packing runs in the library's host code, every step of the
+attention path runs in the library's HIP kernels.  PyTorch supplies device
+memory and the stream.  There is no CPU fallback: a missing library raises.
+"""
+from .binding import (BF16, F32, BllmError, LayerDesc, PrefixGroups, lib_path, load_library,
+                      lse_merge, prefix_group_create, shared_prefix_attention, suffix_attention,
+                      prefix_shared_attention)
+
+__all__ = ["BF16", "F32", "BllmError", "LayerDesc", "PrefixGroups", "lib_path", "load_library", "lse_merge",
+           "prefix_group_create", "shared_prefix_attention", "suffix_attention", "prefix_shared_attention"]

@@ -1,0 +1,205 @@
+"""ctypes binding of libbllm.so: same names as the C entry points, argument
+marshalling only."""
+import ctypes as C
+import os
+
+import numpy as np
+
+F32 = 0
+BF16 = 1
+ITEM_INTS = 8
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+EXPORTS = ["bllm_prefix_group_create", "bllm_prefix_group_create_host", "bllm_prefix_group_metadata",
+           "bllm_prefix_group_destroy", "bllm_shared_prefix_attention", "bllm_suffix_attention", "bllm_lse_merge",
+           "bllm_last_error", "bllm_version"]
+
+
+class BllmError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__("bllm error %d: %s" % (code, text))
+        self.code = code
+
+
+class LayerDesc(C.Structure):
+    _fields_ = [("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("dtype", C.c_int32), ("softmax_scale", C.c_float)]
+
+
+_I32P = C.POINTER(C.c_int32)
+
+
+class PackingView(C.Structure):
+    _fields_ = [("n_groups", C.c_int32), ("n_requests", C.c_int32), ("n_rows", C.c_int32), ("n_active", C.c_int32),
+                ("perm_req", _I32P), ("req_row_start", _I32P), ("group_req_start", _I32P),
+                ("group_row_start", _I32P), ("group_decode_rows", _I32P), ("prefix_kv_start", _I32P),
+                ("req_kv_start", _I32P), ("row_req", _I32P), ("row_pos", _I32P), ("row_src", _I32P),
+                ("n_prefix_tile_items", C.c_int32), ("prefix_tile_items", _I32P),
+                ("n_prefix_row_items", C.c_int32), ("prefix_row_items", _I32P),
+                ("n_suffix_tile_items", C.c_int32), ("suffix_tile_items", _I32P),
+                ("n_suffix_row_items", C.c_int32), ("suffix_row_items", _I32P),
+                ("tile_rows", C.c_int32), ("prefix_split_len", C.c_int32), ("suffix_split_len", C.c_int32),
+                ("n_prefix_ws_rows", C.c_int32), ("n_suffix_ws_rows", C.c_int32),
+                ("prefix_row_split", _I32P), ("suffix_row_split", _I32P)]
+
+
+def lib_path():
+    return os.path.join(_HERE, "libbllm.so")
+
+
+def load_library():
+    """Load libbllm.so; build it first if it is not there.  Raises if that fails."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = lib_path()
+    if not os.path.exists(path):
+        from . import build
+        build.build_library(verbose=False)
+    lib = C.CDLL(path)
+    h = C.c_void_p
+    lib.bllm_prefix_group_create.argtypes = [C.POINTER(LayerDesc), C.c_int32, _I32P, C.c_int32, _I32P, _I32P, _I32P,
+                                             C.c_void_p, C.POINTER(h)]
+    lib.bllm_prefix_group_create_host.argtypes = [C.POINTER(LayerDesc), C.c_int32, _I32P, C.c_int32, _I32P, _I32P,
+                                                  _I32P, C.POINTER(h)]
+    lib.bllm_prefix_group_metadata.argtypes = [h, C.POINTER(PackingView)]
+    lib.bllm_prefix_group_destroy.argtypes = [h]
+    for name in ("bllm_shared_prefix_attention", "bllm_suffix_attention"):
+        getattr(lib, name).argtypes = [h, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.bllm_lse_merge.argtypes = [h, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                   C.c_void_p]
+    for name in EXPORTS[:7]:
+        getattr(lib, name).restype = C.c_int
+    lib.bllm_last_error.restype = C.c_char_p
+    lib.bllm_version.restype = C.c_char_p
+    _LIB = lib
+    return lib
+
+
+def _check(rc):
+    if rc != 0:
+        raise BllmError(rc, load_library().bllm_last_error().decode())
+
+
+def _i32(x):
+    a = np.ascontiguousarray(np.asarray(x), dtype=np.int32)
+    return a, a.ctypes.data_as(_I32P)
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if hasattr(t, "data_ptr"):
+        return C.c_void_p(t.data_ptr())
+    return C.c_void_p(int(t))
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    if hasattr(stream, "cuda_stream"):
+        return C.c_void_p(stream.cuda_stream)
+    return C.c_void_p(int(stream))
+
+
+class PrefixGroups:
+    """Owns a bllm_prefix_groups handle."""
+
+    def __init__(self, handle, desc):
+        self._h = handle
+        self.desc = desc
+        self._meta = None
+
+    @property
+    def handle(self):
+        return self._h
+
+    def metadata(self):
+        """Copies of the handle's host packing arrays, as a dict of int32 numpy arrays / ints."""
+        if self._meta is not None:
+            return self._meta
+        v = PackingView()
+        _check(load_library().bllm_prefix_group_metadata(self._h, C.byref(v)))
+
+        def arr(p, n):
+            return np.ctypeslib.as_array(p, shape=(n,)).copy() if n > 0 else np.zeros(0, np.int32)
+
+        g, r, t, a = v.n_groups, v.n_requests, v.n_rows, v.n_active
+        m = {"n_groups": g, "n_requests": r, "n_rows": t, "n_active": a,
+             "perm_req": arr(v.perm_req, a), "req_row_start": arr(v.req_row_start, a + 1),
+             "group_req_start": arr(v.group_req_start, g + 1), "group_row_start": arr(v.group_row_start, g + 1),
+             "group_decode_rows": arr(v.group_decode_rows, g), "prefix_kv_start": arr(v.prefix_kv_start, g + 1),
+             "req_kv_start": arr(v.req_kv_start, r + 1), "row_req": arr(v.row_req, t), "row_pos": arr(v.row_pos, t),
+             "row_src": arr(v.row_src, t),
+             "tile_rows": v.tile_rows, "prefix_split_len": v.prefix_split_len,
+             "suffix_split_len": v.suffix_split_len, "n_prefix_ws_rows": v.n_prefix_ws_rows,
+             "n_suffix_ws_rows": v.n_suffix_ws_rows,
+             "prefix_row_split": arr(v.prefix_row_split, 3 * t).reshape(t, 3),
+             "suffix_row_split": arr(v.suffix_row_split, 3 * t).reshape(t, 3)}
+        for name in ("prefix_tile_items", "prefix_row_items", "suffix_tile_items", "suffix_row_items"):
+            n = getattr(v, "n_" + name)
+            m[name] = arr(getattr(v, name), n * ITEM_INTS).reshape(n, ITEM_INTS)
+        self._meta = m
+        return m
+
+    def destroy(self):
+        if self._h is not None:
+            h, self._h = self._h, None
+            _check(load_library().bllm_prefix_group_destroy(h))
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def _make_desc(n_q_heads, n_kv_heads, head_dim, dtype, softmax_scale=0.0):
+    return LayerDesc(int(n_q_heads), int(n_kv_heads), int(head_dim), int(dtype), float(softmax_scale))
+
+
+def prefix_group_create(desc, prefix_len, req_group, req_suffix_len, req_q_len, stream=None, host_only=False):
+    """bllm_prefix_group_create (or bllm_prefix_group_create_host with host_only=True).
+    desc: LayerDesc or a tuple (n_q_heads, n_kv_heads, head_dim, dtype[, scale])."""
+    lib = load_library()
+    if not isinstance(desc, LayerDesc):
+        desc = _make_desc(*desc)
+    pl, plp = _i32(prefix_len)
+    rg, rgp = _i32(req_group)
+    rs, rsp = _i32(req_suffix_len)
+    rq, rqp = _i32(req_q_len)
+    if not (len(rg) == len(rs) == len(rq)):
+        raise ValueError("request arrays differ in length")
+    h = C.c_void_p()
+    if host_only:
+        _check(lib.bllm_prefix_group_create_host(C.byref(desc), len(pl), plp, len(rg), rgp, rsp, rqp, C.byref(h)))
+    else:
+        _check(lib.bllm_prefix_group_create(C.byref(desc), len(pl), plp, len(rg), rgp, rsp, rqp, _stream(stream),
+                                            C.byref(h)))
+    return PrefixGroups(h, desc)
+
+
+def shared_prefix_attention(pg, q, k_prefix, v_prefix, o_part, lse_part, stream=None):
+    _check(load_library().bllm_shared_prefix_attention(pg.handle, _ptr(q), _ptr(k_prefix), _ptr(v_prefix),
+                                                       _ptr(o_part), _ptr(lse_part), _stream(stream)))
+
+
+def suffix_attention(pg, q, k_suffix, v_suffix, o_part, lse_part, stream=None):
+    _check(load_library().bllm_suffix_attention(pg.handle, _ptr(q), _ptr(k_suffix), _ptr(v_suffix), _ptr(o_part),
+                                                _ptr(lse_part), _stream(stream)))
+
+
+def lse_merge(pg, o_a, lse_a, o_b, lse_b, o_out, lse_out=None, stream=None):
+    _check(load_library().bllm_lse_merge(pg.handle, _ptr(o_a), _ptr(lse_a), _ptr(o_b), _ptr(lse_b), _ptr(o_out),
+                                         _ptr(lse_out), _stream(stream)))
+
+
+def prefix_shared_attention(pg, q, k_prefix, v_prefix, k_suffix, v_suffix, bufs, stream=None):
+    """The three device calls in sequence on one stream.  bufs: dict with preallocated
+    o1, l1, o2, l2 (fp32 partials), o (layer dtype) and optionally lse."""
+    shared_prefix_attention(pg, q, k_prefix, v_prefix, bufs["o1"], bufs["l1"], stream)
+    suffix_attention(pg, q, k_suffix, v_suffix, bufs["o2"], bufs["l2"], stream)
+    lse_merge(pg, bufs["o1"], bufs["l1"], bufs["o2"], bufs["l2"], bufs["o"], bufs.get("lse"), stream)

@@ -1,0 +1,300 @@
+// C ABI of libbllm: argument validation, handle life cycle, and the sequence of
+// kernel launches behind each call.  See include/bllm.h for the contract.
+#include <cmath>
+#include <cstring>
+#include <new>
+
+#include "bllm_internal.h"
+
+namespace bllm {
+
+static thread_local std::string g_last_error;
+
+void set_error(const std::string& msg) { g_last_error = msg; }
+
+namespace {
+
+int check_desc(const bllm_layer_desc* d) {
+    if (!d) {
+        set_error("null layer descriptor");
+        return BLLM_INVALID_ARG;
+    }
+    if (d->n_q_heads < 1 || d->n_kv_heads < 1 || d->head_dim < 1 || d->n_q_heads % d->n_kv_heads != 0) {
+        set_error("head counts must be positive and n_kv_heads must divide n_q_heads");
+        return BLLM_INVALID_ARG;
+    }
+    if (!(d->softmax_scale >= 0.0f) || std::isinf(d->softmax_scale)) {
+        set_error("softmax_scale must be finite and >= 0");
+        return BLLM_INVALID_ARG;
+    }
+    if (d->dtype != BLLM_F32 && d->dtype != BLLM_BF16) {
+        set_error("unsupported dtype " + std::to_string(d->dtype));
+        return BLLM_UNSUPPORTED;
+    }
+    const int rho = d->n_q_heads / d->n_kv_heads;
+    if (rho != 1 && rho != 2 && rho != 4 && rho != 8) {
+        set_error("unsupported n_q_heads / n_kv_heads ratio " + std::to_string(rho) + " (need 1, 2, 4 or 8)");
+        return BLLM_UNSUPPORTED;
+    }
+    if (d->head_dim != 64 && d->head_dim != 128) {
+        set_error("unsupported head_dim " + std::to_string(d->head_dim) + " (need 64 or 128)");
+        return BLLM_UNSUPPORTED;
+    }
+    return BLLM_OK;
+}
+
+int hip_fail(hipError_t e, const char* what) {
+    set_error(std::string(what) + ": " + hipGetErrorString(e));
+    return e == hipErrorOutOfMemory ? BLLM_OUT_OF_MEMORY : BLLM_HIP_ERROR;
+}
+
+size_t align256(size_t n) { return (n + 255) & ~static_cast<size_t>(255); }
+
+int create_common(const bllm_layer_desc* desc, int32_t n_groups, const int32_t* prefix_len, int32_t n_requests,
+                  const int32_t* req_group, const int32_t* req_suffix_len, const int32_t* req_q_len,
+                  bllm_prefix_groups** out) {
+    if (!out) {
+        set_error("null output handle pointer");
+        return BLLM_INVALID_ARG;
+    }
+    int rc = check_desc(desc);
+    if (rc != BLLM_OK) return rc;
+    bllm_prefix_groups* pg = new (std::nothrow) bllm_prefix_groups();
+    if (!pg) {
+        set_error("host allocation failed");
+        return BLLM_OUT_OF_MEMORY;
+    }
+    pg->desc = *desc;
+    pg->scale = desc->softmax_scale > 0.0f ? desc->softmax_scale : 1.0f / std::sqrt(static_cast<float>(desc->head_dim));
+    try {
+        rc = build_packing(*desc, n_groups, prefix_len, n_requests, req_group, req_suffix_len, req_q_len, &pg->pk);
+    } catch (const std::bad_alloc&) {
+        set_error("host allocation failed while packing");
+        rc = BLLM_OUT_OF_MEMORY;
+    }
+    if (rc != BLLM_OK) {
+        delete pg;
+        return rc;
+    }
+    *out = pg;
+    return BLLM_OK;
+}
+
+template <typename T>
+size_t bytes_of(const std::vector<T>& v) {
+    return align256(v.size() * sizeof(T));
+}
+
+int upload(bllm_prefix_groups* pg, hipStream_t stream) {
+    Packing& p = pg->pk;
+    hipError_t e = hipGetDevice(&pg->device);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    const size_t row_elems = static_cast<size_t>(pg->desc.n_q_heads) * pg->desc.head_dim;
+    const size_t ws_rows = static_cast<size_t>(std::max(p.n_prefix_ws_rows, p.n_suffix_ws_rows));
+    const size_t sizes[8] = {bytes_of(p.prefix_tile_items), bytes_of(p.prefix_row_items), bytes_of(p.suffix_tile_items),
+                             bytes_of(p.suffix_row_items),  bytes_of(p.prefix_row_split), bytes_of(p.suffix_row_split),
+                             align256(ws_rows * row_elems * sizeof(float)),
+                             align256(ws_rows * pg->desc.n_q_heads * sizeof(float))};
+    size_t total = 256;
+    for (size_t s : sizes) total += s;
+    e = hipMalloc(&pg->dev_blob, total);
+    if (e != hipSuccess) return hip_fail(e, "hipMalloc(metadata + split workspace)");
+    char* base = static_cast<char*>(pg->dev_blob);
+    size_t off = 0;
+    auto place = [&](size_t n) {
+        char* ptr = base + off;
+        off += n;
+        return ptr;
+    };
+    pg->d.prefix_tile_items = reinterpret_cast<Item*>(place(sizes[0]));
+    pg->d.prefix_row_items = reinterpret_cast<Item*>(place(sizes[1]));
+    pg->d.suffix_tile_items = reinterpret_cast<Item*>(place(sizes[2]));
+    pg->d.suffix_row_items = reinterpret_cast<Item*>(place(sizes[3]));
+    pg->d.prefix_row_split = reinterpret_cast<RowSplit*>(place(sizes[4]));
+    pg->d.suffix_row_split = reinterpret_cast<RowSplit*>(place(sizes[5]));
+    pg->d.ws_o = reinterpret_cast<float*>(place(sizes[6]));
+    pg->d.ws_lse = reinterpret_cast<float*>(place(sizes[7]));
+
+    auto copy = [&](void* dst, const void* src, size_t n) -> hipError_t {
+        if (n == 0) return hipSuccess;
+        return hipMemcpyAsync(dst, src, n, hipMemcpyHostToDevice, stream);
+    };
+#define BLLM_UP(dst, vec)                                                                   \
+    do {                                                                                    \
+        e = copy(dst, vec.data(), vec.size() * sizeof(vec[0]));                             \
+        if (e != hipSuccess) return hip_fail(e, "hipMemcpyAsync(metadata)");                \
+    } while (0)
+    BLLM_UP(pg->d.prefix_tile_items, p.prefix_tile_items);
+    BLLM_UP(pg->d.prefix_row_items, p.prefix_row_items);
+    BLLM_UP(pg->d.suffix_tile_items, p.suffix_tile_items);
+    BLLM_UP(pg->d.suffix_row_items, p.suffix_row_items);
+    BLLM_UP(pg->d.prefix_row_split, p.prefix_row_split);
+    BLLM_UP(pg->d.suffix_row_split, p.suffix_row_split);
+#undef BLLM_UP
+    // The source vectors are pageable, so the copies above are staged; the
+    // synchronisation makes the handle usable from any stream afterwards.
+    e = hipStreamSynchronize(stream);
+    if (e != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
+    pg->on_device = true;
+    return BLLM_OK;
+}
+
+int check_device_call(const bllm_prefix_groups* pg, std::initializer_list<const void*> ptrs) {
+    if (!pg) {
+        set_error("null handle");
+        return BLLM_INVALID_ARG;
+    }
+    if (!pg->on_device) {
+        set_error("handle was created host-only; device calls are not available on it");
+        return BLLM_INVALID_ARG;
+    }
+    if (pg->pk.n_rows > 0)
+        for (const void* p : ptrs)
+            if (!p) {
+                set_error("null tensor pointer");
+                return BLLM_INVALID_ARG;
+            }
+    return BLLM_OK;
+}
+
+LaunchCtx make_ctx(const bllm_prefix_groups* pg, void* hip_stream) {
+    return LaunchCtx{&pg->desc, pg->scale, pg->pk.n_rows, static_cast<hipStream_t>(hip_stream)};
+}
+
+}  // namespace
+}  // namespace bllm
+
+using namespace bllm;
+
+extern "C" {
+
+int bllm_prefix_group_create_host(const bllm_layer_desc* desc, int32_t n_groups, const int32_t* prefix_len,
+                                  int32_t n_requests, const int32_t* req_group, const int32_t* req_suffix_len,
+                                  const int32_t* req_q_len, bllm_prefix_groups** out) {
+    return create_common(desc, n_groups, prefix_len, n_requests, req_group, req_suffix_len, req_q_len, out);
+}
+
+int bllm_prefix_group_create(const bllm_layer_desc* desc, int32_t n_groups, const int32_t* prefix_len,
+                             int32_t n_requests, const int32_t* req_group, const int32_t* req_suffix_len,
+                             const int32_t* req_q_len, void* hip_stream, bllm_prefix_groups** out) {
+    bllm_prefix_groups* pg = nullptr;
+    int rc = create_common(desc, n_groups, prefix_len, n_requests, req_group, req_suffix_len, req_q_len, &pg);
+    if (rc != BLLM_OK) return rc;
+    rc = upload(pg, static_cast<hipStream_t>(hip_stream));
+    if (rc != BLLM_OK) {
+        bllm_prefix_group_destroy(pg);
+        return rc;
+    }
+    *out = pg;
+    return BLLM_OK;
+}
+
+int bllm_prefix_group_metadata(const bllm_prefix_groups* pg, bllm_packing_view* v) {
+    if (!pg || !v) {
+        set_error("null handle or view");
+        return BLLM_INVALID_ARG;
+    }
+    const Packing& p = pg->pk;
+    std::memset(v, 0, sizeof(*v));
+    v->n_groups = p.n_groups;
+    v->n_requests = p.n_requests;
+    v->n_rows = p.n_rows;
+    v->n_active = p.n_active;
+    v->perm_req = p.perm_req.data();
+    v->req_row_start = p.req_row_start.data();
+    v->group_req_start = p.group_req_start.data();
+    v->group_row_start = p.group_row_start.data();
+    v->group_decode_rows = p.group_decode_rows.data();
+    v->prefix_kv_start = p.prefix_kv_start.data();
+    v->req_kv_start = p.req_kv_start.data();
+    v->row_req = p.row_req.data();
+    v->row_pos = p.row_pos.data();
+    v->row_src = p.row_src.data();
+    v->n_prefix_tile_items = static_cast<int32_t>(p.prefix_tile_items.size());
+    v->prefix_tile_items = reinterpret_cast<const int32_t*>(p.prefix_tile_items.data());
+    v->n_prefix_row_items = static_cast<int32_t>(p.prefix_row_items.size());
+    v->prefix_row_items = reinterpret_cast<const int32_t*>(p.prefix_row_items.data());
+    v->n_suffix_tile_items = static_cast<int32_t>(p.suffix_tile_items.size());
+    v->suffix_tile_items = reinterpret_cast<const int32_t*>(p.suffix_tile_items.data());
+    v->n_suffix_row_items = static_cast<int32_t>(p.suffix_row_items.size());
+    v->suffix_row_items = reinterpret_cast<const int32_t*>(p.suffix_row_items.data());
+    v->tile_rows = p.tile_rows;
+    v->prefix_split_len = p.prefix_split_len;
+    v->suffix_split_len = p.suffix_split_len;
+    v->n_prefix_ws_rows = p.n_prefix_ws_rows;
+    v->n_suffix_ws_rows = p.n_suffix_ws_rows;
+    v->prefix_row_split = reinterpret_cast<const int32_t*>(p.prefix_row_split.data());
+    v->suffix_row_split = reinterpret_cast<const int32_t*>(p.suffix_row_split.data());
+    return BLLM_OK;
+}
+
+int bllm_prefix_group_destroy(bllm_prefix_groups* pg) {
+    if (!pg) return BLLM_OK;
+    int rc = BLLM_OK;
+    if (pg->dev_blob) {
+        hipError_t e = hipFree(pg->dev_blob);
+        if (e != hipSuccess) rc = hip_fail(e, "hipFree");
+    }
+    delete pg;
+    return rc;
+}
+
+static int run_pass(const bllm_prefix_groups* pg, bool prefix, const void* q, const void* k, const void* v,
+                    float* o_part, float* lse_part, void* hip_stream) {
+    int rc = check_device_call(pg, {q, o_part, lse_part});
+    if (rc != BLLM_OK) return rc;
+    const Packing& p = pg->pk;
+    if (p.n_rows == 0) return BLLM_OK;
+    const auto& tiles = prefix ? p.prefix_tile_items : p.suffix_tile_items;
+    const auto& rows = prefix ? p.prefix_row_items : p.suffix_row_items;
+    const int64_t kv_rows = prefix ? p.prefix_kv_start.back() : p.req_kv_start.back();
+    if (kv_rows > 0 && (!k || !v)) {
+        set_error("null KV pointer");
+        return BLLM_INVALID_ARG;
+    }
+    LaunchCtx c = make_ctx(pg, hip_stream);
+    hipError_t e;
+    if (!tiles.empty()) {
+        e = launch_tile_attention(c, prefix ? pg->d.prefix_tile_items : pg->d.suffix_tile_items,
+                                  static_cast<int32_t>(tiles.size()), q, k, v, o_part, lse_part, pg->d.ws_o, pg->d.ws_lse);
+        if (e != hipSuccess) return hip_fail(e, "tile attention launch");
+    }
+    if (!rows.empty()) {
+        e = launch_stream_attention(c, prefix ? pg->d.prefix_row_items : pg->d.suffix_row_items,
+                                    static_cast<int32_t>(rows.size()), q, k, v, o_part, lse_part, pg->d.ws_o, pg->d.ws_lse);
+        if (e != hipSuccess) return hip_fail(e, "streaming attention launch");
+    }
+    if (prefix ? p.prefix_has_split : p.suffix_has_split) {
+        e = launch_split_combine(c, prefix ? pg->d.prefix_row_split : pg->d.suffix_row_split, pg->d.ws_o, pg->d.ws_lse,
+                                 o_part, lse_part);
+        if (e != hipSuccess) return hip_fail(e, "split combine launch");
+    }
+    return BLLM_OK;
+}
+
+int bllm_shared_prefix_attention(const bllm_prefix_groups* pg, const void* q, const void* k_prefix,
+                                 const void* v_prefix, float* o_part, float* lse_part, void* hip_stream) {
+    return run_pass(pg, true, q, k_prefix, v_prefix, o_part, lse_part, hip_stream);
+}
+
+int bllm_suffix_attention(const bllm_prefix_groups* pg, const void* q, const void* k_suffix, const void* v_suffix,
+                          float* o_part, float* lse_part, void* hip_stream) {
+    return run_pass(pg, false, q, k_suffix, v_suffix, o_part, lse_part, hip_stream);
+}
+
+int bllm_lse_merge(const bllm_prefix_groups* pg, const float* o_a, const float* lse_a, const float* o_b,
+                   const float* lse_b, void* o_out, float* lse_out, void* hip_stream) {
+    int rc = check_device_call(pg, {o_a, lse_a, o_b, lse_b, o_out});
+    if (rc != BLLM_OK) return rc;
+    if (pg->pk.n_rows == 0) return BLLM_OK;
+    LaunchCtx c = make_ctx(pg, hip_stream);
+    hipError_t e = launch_lse_merge(c, o_a, lse_a, o_b, lse_b, o_out, lse_out);
+    if (e != hipSuccess) return hip_fail(e, "lse merge launch");
+    return BLLM_OK;
+}
+
+const char* bllm_last_error(void) { return g_last_error.c_str(); }
+
+const char* bllm_version(void) { return "bllm 0.1 (gfx950)"; }
+
+}  // extern "C"

@@ -1,0 +1,95 @@
+// Internal declarations shared by the host side (packing, validation, C ABI)
+// and the kernel launchers.  Not installed; the public contract is include/bllm.h.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "bllm.h"
+
+namespace bllm {
+
+// One unit of kernel work; mirrors bllm_item_field.
+struct Item {
+    int32_t q_row0;
+    int32_t n_rows;
+    int32_t kv_head;
+    int32_t kv_row0;
+    int32_t kv_len;
+    int32_t vis0;
+    int32_t dst_row;
+    int32_t reserved;
+};
+static_assert(sizeof(Item) == BLLM_ITEM_INTS * sizeof(int32_t), "item layout is part of the ABI");
+
+// Per packed row: where its split partials live.
+struct RowSplit {
+    int32_t ws_row0;   // workspace row of split 0
+    int32_t stride;    // workspace rows between consecutive splits
+    int32_t n_splits;  // 0: the pass wrote the row directly
+};
+
+struct Packing {
+    int32_t n_groups = 0, n_requests = 0, n_rows = 0, n_active = 0;
+    std::vector<int32_t> perm_req, req_row_start, group_req_start, group_row_start, group_decode_rows,
+        prefix_kv_start, req_kv_start, row_req, row_pos, row_src;
+    std::vector<Item> prefix_tile_items, prefix_row_items, suffix_tile_items, suffix_row_items;
+    std::vector<RowSplit> prefix_row_split, suffix_row_split;
+    int32_t tile_rows = 0, prefix_split_len = 0, suffix_split_len = 0;
+    int32_t n_prefix_ws_rows = 0, n_suffix_ws_rows = 0;
+    bool prefix_has_split = false, suffix_has_split = false;
+};
+
+struct DeviceLists {
+    Item* prefix_tile_items = nullptr;
+    Item* prefix_row_items = nullptr;
+    Item* suffix_tile_items = nullptr;
+    Item* suffix_row_items = nullptr;
+    RowSplit* prefix_row_split = nullptr;
+    RowSplit* suffix_row_split = nullptr;
+    float* ws_o = nullptr;     // [ws_rows, Hq, D]
+    float* ws_lse = nullptr;   // [ws_rows, Hq]
+};
+
+}  // namespace bllm
+
+struct bllm_prefix_groups {
+    bllm_layer_desc desc;
+    float scale;
+    bllm::Packing pk;
+    bool on_device = false;
+    int device = -1;
+    void* dev_blob = nullptr;          // one allocation holding every device list
+    bllm::DeviceLists d;
+};
+
+namespace bllm {
+
+void set_error(const std::string& msg);
+
+// packing (host)
+int build_packing(const bllm_layer_desc& desc, int32_t n_groups, const int32_t* prefix_len, int32_t n_requests,
+                  const int32_t* req_group, const int32_t* req_suffix_len, const int32_t* req_q_len, Packing* out);
+
+// Kernel launchers (bllm_kernels.hip).  All return hipError_t of the launch.
+struct LaunchCtx {
+    const bllm_layer_desc* desc;
+    float scale;
+    int32_t n_rows;
+    hipStream_t stream;
+};
+
+hipError_t launch_stream_attention(const LaunchCtx& c, const Item* items, int32_t n_items, const void* q,
+                                   const void* k, const void* v, float* o_part, float* lse_part, float* ws_o,
+                                   float* ws_lse);
+hipError_t launch_tile_attention(const LaunchCtx& c, const Item* items, int32_t n_items, const void* q, const void* k,
+                                 const void* v, float* o_part, float* lse_part, float* ws_o, float* ws_lse);
+hipError_t launch_split_combine(const LaunchCtx& c, const RowSplit* row_split, const float* ws_o, const float* ws_lse,
+                                float* o_part, float* lse_part);
+hipError_t launch_lse_merge(const LaunchCtx& c, const float* o_a, const float* lse_a, const float* o_b,
+                            const float* lse_b, void* o_out, float* lse_out);
+
+}  // namespace bllm

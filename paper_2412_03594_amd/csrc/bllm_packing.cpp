@@ -1,0 +1,226 @@
+// Host-side token-batch packing: from prefix-sharing groups and per-request
+// (suffix length, query rows) to the packed row order, the offset arrays and the
+// kernel work lists (BatchLLM Sec. 3.3.1: a token-batch mixes decode tokens and
+// prefill chunks of requests scheduled group by group; Sec. 3.4: per-request
+// metadata separates the shared prefix from the distinct part).
+#include <algorithm>
+#include <limits>
+
+#include "bllm_internal.h"
+
+namespace bllm {
+
+namespace {
+
+constexpr int kTileStackedRows = 256;   // query rows x heads-per-KV-head handled by one MFMA workgroup
+constexpr int kKvTile = 64;             // KV rows per MFMA inner step; split lengths are multiples of it
+constexpr int kSplitWhenBelow = 512;    // split the prefix when fewer tile items than this exist
+constexpr int kSplitTargetItems = 1024;
+constexpr int kMinSplitLen = 256;
+
+bool fits_i32(int64_t v) { return v >= 0 && v <= std::numeric_limits<int32_t>::max(); }
+
+int32_t ceil_div(int32_t a, int32_t b) { return (a + b - 1) / b; }
+
+}  // namespace
+
+int build_packing(const bllm_layer_desc& desc, int32_t n_groups, const int32_t* prefix_len, int32_t n_requests,
+                  const int32_t* req_group, const int32_t* req_suffix_len, const int32_t* req_q_len, Packing* out) {
+    if (n_groups < 1 || n_requests < 0) {
+        set_error("n_groups must be >= 1 and n_requests >= 0");
+        return BLLM_INVALID_ARG;
+    }
+    if (!prefix_len || (n_requests > 0 && (!req_group || !req_suffix_len || !req_q_len))) {
+        set_error("null length array");
+        return BLLM_INVALID_ARG;
+    }
+    Packing& p = *out;
+    p = Packing();
+    p.n_groups = n_groups;
+    p.n_requests = n_requests;
+    const int32_t rho = desc.n_q_heads / desc.n_kv_heads;
+    const int32_t n_kv_heads = desc.n_kv_heads;
+
+    // ---- user-order offsets, with overflow checks -------------------------------------------
+    p.prefix_kv_start.assign(n_groups + 1, 0);
+    int64_t acc = 0;
+    for (int32_t g = 0; g < n_groups; ++g) {
+        if (prefix_len[g] < 0) {
+            set_error("negative prefix length in group " + std::to_string(g));
+            return BLLM_INVALID_ARG;
+        }
+        acc += prefix_len[g];
+        if (!fits_i32(acc)) {
+            set_error("total prefix KV rows overflow int32");
+            return BLLM_INVALID_ARG;
+        }
+        p.prefix_kv_start[g + 1] = static_cast<int32_t>(acc);
+    }
+    p.req_kv_start.assign(n_requests + 1, 0);
+    std::vector<int32_t> user_row_start(n_requests + 1, 0);
+    int64_t kv_acc = 0, row_acc = 0;
+    for (int32_t r = 0; r < n_requests; ++r) {
+        if (req_group[r] < 0 || req_group[r] >= n_groups) {
+            set_error("request " + std::to_string(r) + ": group id out of range");
+            return BLLM_INVALID_ARG;
+        }
+        if (req_suffix_len[r] < 0 || req_q_len[r] < 0 || req_q_len[r] > req_suffix_len[r]) {
+            set_error("request " + std::to_string(r) + ": need 0 <= q_len <= suffix_len");
+            return BLLM_INVALID_ARG;
+        }
+        kv_acc += req_suffix_len[r];
+        row_acc += req_q_len[r];
+        if (!fits_i32(kv_acc) || !fits_i32(row_acc * desc.n_q_heads)) {
+            set_error("suffix KV rows or query rows overflow int32");
+            return BLLM_INVALID_ARG;
+        }
+        p.req_kv_start[r + 1] = static_cast<int32_t>(kv_acc);
+        user_row_start[r + 1] = static_cast<int32_t>(row_acc);
+    }
+    p.n_rows = static_cast<int32_t>(row_acc);
+
+    // ---- packed request order: counting sort on (group, decode-before-chunk) -----------------
+    // Requests are visited in user order, so equal keys keep their user order.
+    std::vector<int32_t> bucket(2 * static_cast<size_t>(n_groups) + 1, 0);
+    for (int32_t r = 0; r < n_requests; ++r) {
+        if (req_q_len[r] == 0) continue;
+        const int32_t key = 2 * req_group[r] + (req_q_len[r] == 1 ? 0 : 1);
+        ++bucket[key + 1];
+    }
+    for (size_t k = 1; k < bucket.size(); ++k) bucket[k] += bucket[k - 1];
+    p.n_active = bucket.back();
+    p.perm_req.assign(p.n_active, 0);
+    {
+        std::vector<int32_t> cursor(bucket.begin(), bucket.end() - 1);
+        for (int32_t r = 0; r < n_requests; ++r) {
+            if (req_q_len[r] == 0) continue;
+            const int32_t key = 2 * req_group[r] + (req_q_len[r] == 1 ? 0 : 1);
+            p.perm_req[cursor[key]++] = r;
+        }
+    }
+    p.group_req_start.assign(n_groups + 1, 0);
+    p.group_decode_rows.assign(n_groups, 0);
+    for (int32_t g = 0; g < n_groups; ++g) {
+        p.group_req_start[g] = bucket[2 * g];
+        p.group_decode_rows[g] = bucket[2 * g + 1] - bucket[2 * g];   // one row per decode request
+    }
+    p.group_req_start[n_groups] = p.n_active;
+
+    // ---- rows --------------------------------------------------------------------------------
+    p.req_row_start.assign(p.n_active + 1, 0);
+    p.row_req.resize(p.n_rows);
+    p.row_pos.resize(p.n_rows);
+    p.row_src.resize(p.n_rows);
+    int32_t t = 0;
+    for (int32_t a = 0; a < p.n_active; ++a) {
+        const int32_t r = p.perm_req[a];
+        const int32_t nq = req_q_len[r];
+        const int32_t first_pos = req_suffix_len[r] - nq;
+        for (int32_t i = 0; i < nq; ++i, ++t) {
+            p.row_req[t] = r;
+            p.row_pos[t] = first_pos + i;
+            p.row_src[t] = user_row_start[r] + i;
+        }
+        p.req_row_start[a + 1] = t;
+    }
+    p.group_row_start.assign(n_groups + 1, 0);
+    for (int32_t g = 0; g < n_groups; ++g) p.group_row_start[g] = p.req_row_start[p.group_req_start[g]];
+    p.group_row_start[n_groups] = p.n_rows;
+
+    // ---- work lists --------------------------------------------------------------------------
+    const bool mfma = desc.dtype == BLLM_BF16 && desc.head_dim == 128;
+    p.tile_rows = mfma ? kTileStackedRows / rho : 0;
+    p.prefix_row_split.assign(p.n_rows, RowSplit{0, 0, 0});
+    p.suffix_row_split.assign(p.n_rows, RowSplit{0, 0, 0});
+
+    if (mfma) {
+        const int32_t br = p.tile_rows;
+        // Split long prefixes when the batch alone cannot fill the chip.
+        int64_t base_items = 0;
+        int32_t max_lp = 0;
+        for (int32_t g = 0; g < n_groups; ++g) {
+            const int32_t rows = p.group_row_start[g + 1] - p.group_row_start[g];
+            if (rows == 0 || prefix_len[g] == 0) continue;
+            base_items += static_cast<int64_t>(ceil_div(rows, br)) * n_kv_heads;
+            max_lp = std::max(max_lp, prefix_len[g]);
+        }
+        p.prefix_split_len = 0;
+        if (base_items > 0 && base_items < kSplitWhenBelow) {
+            const int32_t want = static_cast<int32_t>((kSplitTargetItems + base_items - 1) / base_items);
+            int32_t len = ceil_div(ceil_div(max_lp, want), kKvTile) * kKvTile;
+            len = std::max(len, kMinSplitLen);
+            if (len < max_lp) p.prefix_split_len = len;
+        }
+        int64_t ws_rows = 0;
+        for (int32_t g = 0; g < n_groups; ++g) {
+            const int32_t row0 = p.group_row_start[g];
+            const int32_t rows = p.group_row_start[g + 1] - row0;
+            if (rows == 0) continue;
+            const int32_t lp = prefix_len[g];
+            const int32_t n_sp = (p.prefix_split_len > 0 && lp > p.prefix_split_len) ? ceil_div(lp, p.prefix_split_len) : 1;
+            const int32_t ws_base = static_cast<int32_t>(ws_rows);
+            if (n_sp > 1) {
+                ws_rows += static_cast<int64_t>(rows) * n_sp;
+                if (!fits_i32(ws_rows * desc.n_q_heads)) {
+                    set_error("prefix split workspace overflows int32 rows");
+                    return BLLM_INVALID_ARG;
+                }
+                for (int32_t i = 0; i < rows; ++i) p.prefix_row_split[row0 + i] = RowSplit{ws_base + i, rows, n_sp};
+                p.prefix_has_split = true;
+            }
+            for (int32_t c = 0; c < n_sp; ++c) {
+                const int32_t kv_off = (n_sp > 1) ? c * p.prefix_split_len : 0;
+                const int32_t kv_len = (n_sp > 1) ? std::min(p.prefix_split_len, lp - kv_off) : lp;
+                for (int32_t i0 = 0; i0 < rows; i0 += br) {
+                    for (int32_t j = 0; j < n_kv_heads; ++j) {
+                        Item it;
+                        it.q_row0 = row0 + i0;
+                        it.n_rows = std::min(br, rows - i0);
+                        it.kv_head = j;
+                        it.kv_row0 = p.prefix_kv_start[g] + kv_off;
+                        it.kv_len = kv_len;
+                        it.vis0 = kv_len;
+                        it.dst_row = (n_sp > 1) ? ws_base + c * rows + i0 : -1;
+                        it.reserved = 0;
+                        p.prefix_tile_items.push_back(it);
+                    }
+                }
+            }
+        }
+        p.n_prefix_ws_rows = static_cast<int32_t>(ws_rows);
+
+        for (int32_t a = 0; a < p.n_active; ++a) {
+            const int32_t r = p.perm_req[a];
+            const int32_t nq = req_q_len[r];
+            const int32_t s = req_suffix_len[r];
+            const int32_t row0 = p.req_row_start[a];
+            if (nq == 1) {
+                for (int32_t j = 0; j < n_kv_heads; ++j)
+                    p.suffix_row_items.push_back(Item{row0, 1, j, p.req_kv_start[r], s, s, -1, 0});
+            } else {
+                for (int32_t i0 = 0; i0 < nq; i0 += br) {
+                    const int32_t n = std::min(br, nq - i0);
+                    for (int32_t j = 0; j < n_kv_heads; ++j)
+                        p.suffix_tile_items.push_back(
+                            Item{row0 + i0, n, j, p.req_kv_start[r], s - nq + i0 + n, s - nq + i0 + 1, -1, 0});
+                }
+            }
+        }
+    } else {
+        // No MFMA path for this dtype / head_dim: every row streams its keys.
+        for (int32_t g = 0; g < n_groups; ++g) {
+            for (int32_t tt = p.group_row_start[g]; tt < p.group_row_start[g + 1]; ++tt)
+                for (int32_t j = 0; j < n_kv_heads; ++j)
+                    p.prefix_row_items.push_back(
+                        Item{tt, 1, j, p.prefix_kv_start[g], prefix_len[g], prefix_len[g], -1, 0});
+        }
+        for (int32_t tt = 0; tt < p.n_rows; ++tt) {
+            const int32_t r = p.row_req[tt];
+            for (int32_t j = 0; j < n_kv_heads; ++j)
+                p.suffix_row_items.push_back(Item{tt, 1, j, p.req_kv_start[r], p.row_pos[tt] + 1, p.row_pos[tt] + 1, -1, 0});
+        }
+    }
+    return BLLM_OK;
+}
+
+}  // namespace bllm

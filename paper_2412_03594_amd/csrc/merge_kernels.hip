@@ -1,0 +1,121 @@
+// Online-softmax reductions of partial attention results (BatchLLM Sec. 5:
+// the results of the different parts are reduced through online softmax).
+//   lse_merge_kernel     two partials -> final output in the layer's dtype
+//   split_combine_kernel n partials of one pass (KV split for occupancy) -> that
+//                        pass's fp32 partial
+// Both are pure streaming kernels: every thread owns 4 consecutive head-dim
+// elements of one (row, head) and reads/writes them with 16-byte accesses.
+#include "bllm_device.h"
+#include "bllm_internal.h"
+
+namespace bllm {
+namespace {
+
+constexpr int kMergeThreads = 256;
+
+template <bool kBf16Out>
+__global__ __launch_bounds__(kMergeThreads) void lse_merge_kernel(
+    const float* __restrict__ o_a, const float* __restrict__ lse_a, const float* __restrict__ o_b,
+    const float* __restrict__ lse_b, void* __restrict__ o_out, float* __restrict__ lse_out, int64_t n_row_heads,
+    int quads_per_row_head /* D/4 */) {
+    const int64_t gid = static_cast<int64_t>(blockIdx.x) * kMergeThreads + threadIdx.x;
+    const int64_t rh = gid / quads_per_row_head;
+    if (rh >= n_row_heads) return;
+    const int quad = static_cast<int>(gid - rh * quads_per_row_head);
+    const float la = lse_a[rh];
+    const float lb = lse_b[rh];
+    const float top = fmaxf(la, lb);
+    float wa, wb, inv, lse;
+    if (top == -INFINITY) {            // both parts empty
+        wa = wb = 0.f;
+        inv = 0.f;
+        lse = -INFINITY;
+    } else {
+        wa = expf(la - top);           // exp(-inf) = 0 for an empty part
+        wb = expf(lb - top);
+        const float tot = wa + wb;
+        inv = 1.f / tot;
+        lse = top + logf(tot);
+    }
+    const size_t off = static_cast<size_t>(rh) * quads_per_row_head * 4 + quad * 4;
+    // An empty part's rows are specified as 0, but never multiply garbage by 0.
+    const float4 a = wa > 0.f ? *reinterpret_cast<const float4*>(o_a + off) : make_float4(0.f, 0.f, 0.f, 0.f);
+    const float4 b = wb > 0.f ? *reinterpret_cast<const float4*>(o_b + off) : make_float4(0.f, 0.f, 0.f, 0.f);
+    float4 r;
+    r.x = (wa * a.x + wb * b.x) * inv;
+    r.y = (wa * a.y + wb * b.y) * inv;
+    r.z = (wa * a.z + wb * b.z) * inv;
+    r.w = (wa * a.w + wb * b.w) * inv;
+    if constexpr (kBf16Out) {
+        uint2 packed = make_uint2(pack_bf16(r.x, r.y), pack_bf16(r.z, r.w));
+        *reinterpret_cast<uint2*>(static_cast<uint16_t*>(o_out) + off) = packed;
+    } else {
+        *reinterpret_cast<float4*>(static_cast<float*>(o_out) + off) = r;
+    }
+    if (lse_out != nullptr && quad == 0) lse_out[rh] = lse;
+}
+
+__global__ __launch_bounds__(kMergeThreads) void split_combine_kernel(
+    const RowSplit* __restrict__ row_split, const float* __restrict__ ws_o, const float* __restrict__ ws_lse,
+    float* __restrict__ o_part, float* __restrict__ lse_part, int64_t n_row_heads, int n_q_heads,
+    int quads_per_row_head) {
+    const int64_t gid = static_cast<int64_t>(blockIdx.x) * kMergeThreads + threadIdx.x;
+    const int64_t rh = gid / quads_per_row_head;
+    if (rh >= n_row_heads) return;
+    const int quad = static_cast<int>(gid - rh * quads_per_row_head);
+    const int64_t row = rh / n_q_heads;
+    const int head = static_cast<int>(rh - row * n_q_heads);
+    const RowSplit sp = row_split[row];
+    if (sp.n_splits <= 0) return;      // this row was written directly by the pass
+    float top = -INFINITY;
+    for (int c = 0; c < sp.n_splits; ++c)
+        top = fmaxf(top, ws_lse[(static_cast<size_t>(sp.ws_row0) + static_cast<size_t>(c) * sp.stride) * n_q_heads + head]);
+    float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
+    float den = 0.f;
+    for (int c = 0; c < sp.n_splits; ++c) {
+        const size_t wrh = (static_cast<size_t>(sp.ws_row0) + static_cast<size_t>(c) * sp.stride) * n_q_heads + head;
+        const float w = expf(ws_lse[wrh] - top);
+        const float4 x = *reinterpret_cast<const float4*>(ws_o + wrh * quads_per_row_head * 4 + quad * 4);
+        num.x = fmaf(w, x.x, num.x);
+        num.y = fmaf(w, x.y, num.y);
+        num.z = fmaf(w, x.z, num.z);
+        num.w = fmaf(w, x.w, num.w);
+        den += w;
+    }
+    const float inv = 1.f / den;       // every split of a split row holds at least one key
+    const size_t off = static_cast<size_t>(rh) * quads_per_row_head * 4 + quad * 4;
+    *reinterpret_cast<float4*>(o_part + off) = make_float4(num.x * inv, num.y * inv, num.z * inv, num.w * inv);
+    if (quad == 0) lse_part[rh] = top + logf(den);
+}
+
+}  // namespace
+
+hipError_t launch_lse_merge(const LaunchCtx& c, const float* o_a, const float* lse_a, const float* o_b,
+                            const float* lse_b, void* o_out, float* lse_out) {
+    const int64_t n_row_heads = static_cast<int64_t>(c.n_rows) * c.desc->n_q_heads;
+    const int quads = c.desc->head_dim / 4;
+    const int64_t threads = n_row_heads * quads;
+    if (threads == 0) return hipSuccess;
+    dim3 grid(static_cast<unsigned>((threads + kMergeThreads - 1) / kMergeThreads)), block(kMergeThreads);
+    if (c.desc->dtype == BLLM_BF16)
+        hipLaunchKernelGGL(lse_merge_kernel<true>, grid, block, 0, c.stream, o_a, lse_a, o_b, lse_b, o_out, lse_out,
+                           n_row_heads, quads);
+    else
+        hipLaunchKernelGGL(lse_merge_kernel<false>, grid, block, 0, c.stream, o_a, lse_a, o_b, lse_b, o_out, lse_out,
+                           n_row_heads, quads);
+    return hipGetLastError();
+}
+
+hipError_t launch_split_combine(const LaunchCtx& c, const RowSplit* row_split, const float* ws_o, const float* ws_lse,
+                                float* o_part, float* lse_part) {
+    const int64_t n_row_heads = static_cast<int64_t>(c.n_rows) * c.desc->n_q_heads;
+    const int quads = c.desc->head_dim / 4;
+    const int64_t threads = n_row_heads * quads;
+    if (threads == 0) return hipSuccess;
+    dim3 grid(static_cast<unsigned>((threads + kMergeThreads - 1) / kMergeThreads)), block(kMergeThreads);
+    hipLaunchKernelGGL(split_combine_kernel, grid, block, 0, c.stream, row_split, ws_o, ws_lse, o_part, lse_part,
+                       n_row_heads, c.desc->n_q_heads, quads);
+    return hipGetLastError();
+}
+
+}  // namespace bllm

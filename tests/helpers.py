@@ -1,0 +1,75 @@
+"""Shared plumbing of the GPU parity tests: upload a seeded batch, run the three
+C-ABI calls, bring the results back in USER row order."""
+import numpy as np
+
+import workload
+
+
+def layer_tuple(L, scale=0.0):
+    return (L.n_q_heads, L.n_kv_heads, L.head_dim, L.dtype, scale)
+
+
+def run_hip_path(batch, vals, scale=0.0, want_lse=True, pg=None):
+    import torch
+    import paper_2412_03594_amd as bllm
+    L = batch.layer
+    dev = torch.device("cuda:0")
+    tdt = torch.bfloat16 if L.dtype == workload.BF16 else torch.float32
+    own = pg is None
+    if own:
+        pg = bllm.prefix_group_create(layer_tuple(L, scale), batch.prefix_len, batch.req_group,
+                                      batch.req_suffix_len, batch.req_q_len)
+    meta = pg.metadata()
+    T = meta["n_rows"]
+    up = lambda x: torch.from_numpy(np.ascontiguousarray(x)).to(dev).to(tdt).contiguous()
+    q = up(vals["q"][meta["row_src"]])
+    kp, vp, ks, vs = up(vals["k_prefix"]), up(vals["v_prefix"]), up(vals["k_suffix"]), up(vals["v_suffix"])
+    nan = float("nan")
+    o1 = torch.full((T, L.n_q_heads, L.head_dim), nan, device=dev, dtype=torch.float32)
+    o2 = torch.full_like(o1, nan)
+    l1 = torch.full((T, L.n_q_heads), nan, device=dev, dtype=torch.float32)
+    l2 = torch.full_like(l1, nan)
+    o = torch.full((T, L.n_q_heads, L.head_dim), nan, device=dev, dtype=tdt)
+    lse = torch.full_like(l1, nan) if want_lse else None
+    bllm.shared_prefix_attention(pg, q, kp, vp, o1, l1)
+    bllm.suffix_attention(pg, q, ks, vs, o2, l2)
+    bllm.lse_merge(pg, o1, l1, o2, l2, o, lse)
+    torch.cuda.synchronize()
+    inv = np.empty(T, dtype=np.int64)
+    inv[meta["row_src"]] = np.arange(T)
+    back = lambda t: t.float().cpu().numpy()[inv] if T > 0 else t.float().cpu().numpy()
+    out = {"o": back(o), "o_prefix": back(o1), "lse_prefix": back(l1), "o_suffix": back(o2), "lse_suffix": back(l2),
+           "meta": meta}
+    if want_lse:
+        out["lse"] = back(lse)
+    if own:
+        pg.destroy()
+    return out
+
+
+def run_oracle(batch, vals, scale=None, **kw):
+    from oracle import attention as oa
+    L = batch.layer
+    return oa.prefix_shared_attention(
+        vals["q"], vals["k_prefix"], vals["v_prefix"], vals["k_suffix"], vals["v_suffix"],
+        batch.prefix_len, batch.req_group, batch.req_suffix_len, batch.req_q_len,
+        L.n_q_heads, L.n_kv_heads, scale=scale, **kw)
+
+
+def max_abs_err(got, ref, rows=None):
+    """max |got - ref| where -inf == -inf counts as 0 and any NaN / inf mismatch as inf."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    if rows is not None:
+        got, ref = got[rows], ref[rows]
+    if got.size == 0:
+        return 0.0
+    both_ninf = np.isneginf(got) & np.isneginf(ref)
+    d = np.abs(np.where(both_ninf, 0.0, got) - np.where(both_ninf, 0.0, ref))
+    d = np.where(np.isnan(d), np.inf, d)
+    return float(d.max())
+
+
+# Tolerances (max abs error) of the parity bar: fp32 path 1e-5, bf16 inputs with
+# fp32 accumulation 2e-2 (the final output is itself rounded to bf16).
+TOL = {workload.F32: 1e-5, workload.BF16: 2e-2}
