@@ -1,0 +1,258 @@
+#!/usr/bin/env python3
+"""Benchmark of the prefix-shared attention hot path on one MI355X.
+
+A step is one pass of the whole path -- shared-prefix pass, distinct-suffix pass,
+log-sum-exp merge -- over one synthetic token batch that is already resident in
+HBM.  Prints ONE JSON line: tokens/s per layer, the roofline of the dominant
+kernel (HBM for the streaming suffix kernel, MFMA for the prefix tile kernel) and
+the CPU oracle timed on a bounded sample of the same workload.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import numpy as np
+
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+
+
+def algorithmic_work(batch, meta):
+    """Bytes / flops the method must move per step (not what it avoids)."""
+    L = batch.layer
+    e = 2 if L.dtype == 1 else 4
+    hq, hkv, d = L.n_q_heads, L.n_kv_heads, L.head_dim
+    T = batch.n_rows
+    rows_g = np.diff(meta["group_row_start"]).astype(np.float64)
+    lp = batch.prefix_len.astype(np.float64)
+    used = rows_g > 0
+    q_bytes = T * hq * d * e
+    part_bytes = T * hq * (4 * d + 4)
+    prefix = {"bytes": float(2 * (lp * used).sum() * hkv * d * e + q_bytes + part_bytes),
+              "flops": float(4 * (rows_g * lp).sum() * hq * d)}
+    act = batch.req_q_len > 0
+    s = batch.req_suffix_len.astype(np.float64)
+    nq = batch.req_q_len.astype(np.float64)
+    # row i of a request sees s - q + i + 1 suffix keys
+    vis_sum = nq * (s - nq) + nq * (nq + 1) / 2
+    suffix = {"bytes": float(2 * (s * act).sum() * hkv * d * e + q_bytes + part_bytes),
+              "flops": float(4 * hq * d * vis_sum.sum())}
+    merge = {"bytes": float(T * hq * (2 * (4 * d + 4) + e * d)), "flops": 0.0}
+    return {"prefix": prefix, "suffix": suffix, "merge": merge}
+
+
+def time_loop(fn, steps, warmup, torch):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    ev0 = torch.cuda.Event(enable_timing=True)
+    ev1 = torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for _ in range(steps):
+        fn()
+    ev1.record()
+    torch.cuda.synchronize()
+    return ev0.elapsed_time(ev1) / steps      # ms per call
+
+
+def oracle_baseline(batch, vals, budget_s=15.0):
+    """Time the CPU oracle (as it stands, single process) on a bounded stratified
+    sample of requests: one active request per group, round robin, until the budget is used."""
+    from oracle import attention as oa
+    from threadpoolctl import threadpool_info
+    L = batch.layer
+    by_group = {}
+    for r in range(batch.n_requests):
+        if batch.req_q_len[r] > 0:
+            by_group.setdefault(int(batch.req_group[r]), []).append(r)
+    order = []
+    depth = 0
+    while True:
+        layer = [rs[depth] for rs in by_group.values() if depth < len(rs)]
+        if not layer:
+            break
+        order += layer
+        depth += 1
+    done_rows, done_reqs = 0, 0
+    t0 = time.perf_counter()
+    for r in order:
+        oa.prefix_shared_attention(vals["q"], vals["k_prefix"], vals["v_prefix"], vals["k_suffix"], vals["v_suffix"],
+                                   batch.prefix_len, batch.req_group, batch.req_suffix_len, batch.req_q_len,
+                                   L.n_q_heads, L.n_kv_heads, requests=[r], parts=False)
+        done_rows += int(batch.req_q_len[r])
+        done_reqs += 1
+        if time.perf_counter() - t0 > budget_s:
+            break
+    dt = time.perf_counter() - t0
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    return {"value": done_rows / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": "%d of %d active requests (round robin over the %d groups), %d rows, %.1f s" %
+                      (done_reqs, len(order), len(by_group), done_rows, dt)}
+
+
+def run_workload(name, steps, warmup, seed, rotate, torch, bllm, workload, with_values_host=True):
+    batch = workload.CONFIGS[name](seed)
+    L = batch.layer
+    dev = torch.device("cuda:0")
+    tdt = torch.bfloat16 if L.dtype == workload.BF16 else torch.float32
+    pg = bllm.prefix_group_create((L.n_q_heads, L.n_kv_heads, L.head_dim, L.dtype), batch.prefix_len,
+                                  batch.req_group, batch.req_suffix_len, batch.req_q_len)
+    meta = pg.metadata()
+    T = meta["n_rows"]
+    vals = workload.draw_values(batch) if with_values_host else None
+    if vals is not None:
+        up = lambda x: torch.from_numpy(x).to(dev).to(tdt).contiguous()
+        q = up(vals["q"][meta["row_src"]])
+        kv = [[up(vals[n]) for n in ("k_prefix", "v_prefix", "k_suffix", "v_suffix")]]
+    else:
+        g = torch.Generator(device=dev)
+        g.manual_seed(seed)
+        mk = lambda n, h: torch.randn((n, h, L.head_dim), generator=g, device=dev, dtype=torch.float32).to(tdt)
+        q = mk(T, L.n_q_heads)
+        kv = [[mk(batch.n_prefix_kv, L.n_kv_heads), mk(batch.n_prefix_kv, L.n_kv_heads),
+               mk(batch.n_suffix_kv, L.n_kv_heads), mk(batch.n_suffix_kv, L.n_kv_heads)]]
+    # Rotating copies of the KV keep a step from being served out of the 256 MB Infinity Cache.
+    for _ in range(rotate - 1):
+        kv.append([t.clone() for t in kv[0]])
+    o1 = torch.empty((T, L.n_q_heads, L.head_dim), device=dev, dtype=torch.float32)
+    o2 = torch.empty_like(o1)
+    l1 = torch.empty((T, L.n_q_heads), device=dev, dtype=torch.float32)
+    l2 = torch.empty_like(l1)
+    o = torch.empty((T, L.n_q_heads, L.head_dim), device=dev, dtype=tdt)
+    state = {"i": 0}
+
+    def nxt():
+        state["i"] = (state["i"] + 1) % len(kv)
+        return kv[state["i"]]
+
+    def prefix_pass():
+        b = nxt()
+        bllm.shared_prefix_attention(pg, q, b[0], b[1], o1, l1)
+
+    def suffix_pass():
+        b = nxt()
+        bllm.suffix_attention(pg, q, b[2], b[3], o2, l2)
+
+    def merge_pass():
+        bllm.lse_merge(pg, o1, l1, o2, l2, o, None)
+
+    def step():
+        b = nxt()
+        bllm.shared_prefix_attention(pg, q, b[0], b[1], o1, l1)
+        bllm.suffix_attention(pg, q, b[2], b[3], o2, l2)
+        bllm.lse_merge(pg, o1, l1, o2, l2, o, None)
+
+    # whole-step timing: K steps bracketed by synchronisation on both sides
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms_step = (time.perf_counter() - t0) * 1e3 / steps
+
+    # per-pass launch durations with events on the launch stream
+    t_pass = {"prefix": time_loop(prefix_pass, steps, warmup, torch),
+              "suffix": time_loop(suffix_pass, steps, warmup, torch),
+              "merge": time_loop(merge_pass, steps, warmup, torch)}
+    work = algorithmic_work(batch, meta)
+    passes = {}
+    for k in ("prefix", "suffix", "merge"):
+        sec = t_pass[k] * 1e-3
+        passes[k] = {"ms": round(t_pass[k], 5), "GB_s": round(work[k]["bytes"] / sec / 1e9, 1),
+                     "TFLOP_s": round(work[k]["flops"] / sec / 1e12, 2),
+                     "alg_MB": round(work[k]["bytes"] / 1e6, 2), "alg_GFLOP": round(work[k]["flops"] / 1e9, 2)}
+    res = {"batch": batch, "vals": vals, "meta": meta, "ms_step": ms_step, "passes": passes, "work": work,
+           "t_pass": t_pass, "tokens": T}
+    pg.destroy()
+    return res
+
+
+def roofline_of(res):
+    """Roofline record of the pass that takes the most time."""
+    t = res["t_pass"]
+    name = max(("prefix", "suffix", "merge"), key=lambda k: t[k])
+    w = res["work"][name]
+    sec = t[name] * 1e-3
+    # arithmetic intensity decides which roof bounds the pass
+    ai = w["flops"] / max(w["bytes"], 1.0)
+    if name == "prefix" and ai > PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9):
+        a = w["flops"] / sec / 1e12
+        return {"kernel": "tile_attention_kernel (shared-prefix pass)", "bound": "mfma", "achieved": round(a, 2),
+                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(a / PEAK_BF16_TFLOPS, 4), "traffic": None}
+    a = w["bytes"] / sec / 1e9
+    kern = {"prefix": "tile_attention_kernel (shared-prefix pass)",
+            "suffix": "stream_attention_kernel (distinct-suffix pass)", "merge": "lse_merge_kernel"}[name]
+    return {"kernel": kern, "bound": "hbm", "achieved": round(a, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+            "frac": round(a / PEAK_HBM_GBS, 4), "traffic": None}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="l8b_decode")
+    ap.add_argument("--also", default="rank_longprefix,l8b_mixed",
+                    help="comma-separated extra workloads reported under 'other_workloads' ('' for none)")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--rotate", type=int, default=2, help="copies of the KV tensors cycled through")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding or collectives are part of it); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import workload
+    import paper_2412_03594_amd as bllm
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the hot path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    bllm.load_library()
+
+    main_res = run_workload(args.workload, args.steps, args.warmup, args.seed, args.rotate, torch, bllm, workload)
+    batch = main_res["batch"]
+    L = batch.layer
+    out = {
+        "metric": "prefix-shared attention tokens/s per layer",
+        "value": round(main_res["tokens"] / (main_res["ms_step"] * 1e-3), 1),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(main_res["ms_step"], 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if L.dtype == workload.BF16 else "f32",
+        "data": "synthetic",
+        "config": {"workload": args.workload, "seed": args.seed, "n_q_heads": L.n_q_heads,
+                   "n_kv_heads": L.n_kv_heads, "head_dim": L.head_dim, "groups": batch.n_groups,
+                   "requests": batch.n_requests, "token_rows": batch.n_rows,
+                   "prefix_kv_rows": batch.n_prefix_kv, "suffix_kv_rows": batch.n_suffix_kv,
+                   "kv_copies_rotated": args.rotate},
+        "roofline": roofline_of(main_res),
+        "passes": main_res["passes"],
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = oracle_baseline(batch, main_res["vals"])
+    others = {}
+    for name in [n for n in args.also.split(",") if n and n != args.workload]:
+        r = run_workload(name, max(20, args.steps // 4), max(5, args.warmup // 2), args.seed, args.rotate, torch,
+                         bllm, workload)
+        others[name] = {"tokens_per_s": round(r["tokens"] / (r["ms_step"] * 1e-3), 1),
+                        "ms_per_step": round(r["ms_step"], 5), "token_rows": r["tokens"],
+                        "roofline": roofline_of(r), "passes": r["passes"]}
+    if others:
+        out["other_workloads"] = others
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
