@@ -261,7 +261,8 @@ static int run_pass(const bllm_prefix_groups* pg, bool prefix, const void* q, co
     }
     if (!rows.empty()) {
         e = launch_stream_attention(c, prefix ? pg->d.prefix_row_items : pg->d.suffix_row_items,
-                                    static_cast<int32_t>(rows.size()), q, k, v, o_part, lse_part, pg->d.ws_o, pg->d.ws_lse);
+                                    static_cast<int32_t>(rows.size()), prefix ? p.prefix_stream_wpi : p.suffix_stream_wpi, q, k, v,
+                                    o_part, lse_part, pg->d.ws_o, pg->d.ws_lse);
         if (e != hipSuccess) return hip_fail(e, "streaming attention launch");
     }
     if (prefix ? p.prefix_has_split : p.suffix_has_split) {

@@ -41,6 +41,8 @@ struct Packing {
     int32_t tile_rows = 0, prefix_split_len = 0, suffix_split_len = 0;
     int32_t n_prefix_ws_rows = 0, n_suffix_ws_rows = 0;
     bool prefix_has_split = false, suffix_has_split = false;
+    // wavefronts that share one streaming item (1, 2 or 4), per pass
+    int32_t prefix_stream_wpi = 4, suffix_stream_wpi = 4;
 };
 
 struct DeviceLists {
@@ -82,9 +84,9 @@ struct LaunchCtx {
     hipStream_t stream;
 };
 
-hipError_t launch_stream_attention(const LaunchCtx& c, const Item* items, int32_t n_items, const void* q,
-                                   const void* k, const void* v, float* o_part, float* lse_part, float* ws_o,
-                                   float* ws_lse);
+hipError_t launch_stream_attention(const LaunchCtx& c, const Item* items, int32_t n_items, int waves_per_item,
+                                   const void* q, const void* k, const void* v, float* o_part, float* lse_part,
+                                   float* ws_o, float* ws_lse);
 hipError_t launch_tile_attention(const LaunchCtx& c, const Item* items, int32_t n_items, const void* q, const void* k,
                                  const void* v, float* o_part, float* lse_part, float* ws_o, float* ws_lse);
 hipError_t launch_split_combine(const LaunchCtx& c, const RowSplit* row_split, const float* ws_o, const float* ws_lse,

@@ -220,6 +220,20 @@ int build_packing(const bllm_layer_desc& desc, int32_t n_groups, const int32_t* 
                 p.suffix_row_items.push_back(Item{tt, 1, j, p.req_kv_start[r], p.row_pos[tt] + 1, p.row_pos[tt] + 1, -1, 0});
         }
     }
+    // Streaming items: longest first, so that the hardware's in-order workgroup dispatch
+    // balances the ragged lengths; then pick how many wavefronts share an item from the
+    // mean range length (about 64 KV rows or more per wavefront).
+    auto finish_stream_list = [](std::vector<Item>& v, int32_t* wpi) {
+        std::stable_sort(v.begin(), v.end(), [](const Item& a, const Item& b) {
+            return std::min(a.kv_len, a.vis0) > std::min(b.kv_len, b.vis0);
+        });
+        int64_t total = 0;
+        for (const Item& it : v) total += std::min(it.kv_len, it.vis0);
+        const int64_t mean = v.empty() ? 0 : total / static_cast<int64_t>(v.size());
+        *wpi = mean >= 192 ? 4 : mean >= 96 ? 2 : 1;
+    };
+    finish_stream_list(p.prefix_row_items, &p.prefix_stream_wpi);
+    finish_stream_list(p.suffix_row_items, &p.suffix_stream_wpi);
     return BLLM_OK;
 }
 

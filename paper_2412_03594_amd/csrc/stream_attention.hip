@@ -4,11 +4,17 @@
 // Sec. 4.3.3, Sec. 5: a matrix-vector product per request), and the fallback
 // for every row when the dtype / head_dim has no matrix-core path.
 //
-// One workgroup (4 wavefronts) per item.  A KV row is read by 16 lanes, 16 or
-// 32 bytes each, so every wavefront load instruction fetches four whole rows;
-// the workgroup therefore runs 16 independent online-softmax streams over
-// interleaved rows and merges them through LDS at the end.  Dot products are
-// finished with DPP adds inside each 16-lane row; no matrix cores are used.
+// A KV row is read by 16 lanes, 16 or 32 bytes each, so one wavefront load
+// instruction fetches four whole rows and a wavefront runs four independent
+// online-softmax streams over interleaved rows.  WPI wavefronts (1, 2 or 4,
+// chosen by the host from the typical range length) share one item; the
+// streams of a wavefront are merged with lane exchanges, the wavefronts of an
+// item through a few KB of LDS.  Dot products are finished with DPP adds inside
+// each 16-lane row; no matrix cores are used.  In the bf16 instantiation K and
+// V stay packed: q.k uses the 2-way bf16 dot instruction with fp32
+// accumulation, and p.v uses it on row pairs with p rounded to bf16.
+#include <type_traits>
+
 #include "bllm_device.h"
 #include "bllm_internal.h"
 
@@ -16,32 +22,46 @@ namespace bllm {
 namespace {
 
 constexpr int kStreamThreads = 256;
-constexpr int kStreams = 16;       // 4 wavefronts x 4 sixteen-lane rows
-constexpr int kRowsPerStep = 4;    // KV rows each stream handles per loop step
+constexpr int kWavesPerBlock = 4;
+constexpr int kRowsPerStep = 4;    // KV rows each 16-lane stream handles per loop step
 
 template <bool kBf16, int EPL>
-__device__ __forceinline__ void load_chunk(const void* base, size_t elem_off, bool valid, float (&out)[EPL]) {
+struct Chunk;                      // EPL consecutive head-dim elements of one row, as loaded
+
+template <>
+struct Chunk<true, 8> { uint32_t w[4]; };
+template <>
+struct Chunk<true, 4> { uint32_t w[2]; };
+template <>
+struct Chunk<false, 8> { float f[8]; };
+template <>
+struct Chunk<false, 4> { float f[4]; };
+
+template <bool kBf16, int EPL>
+__device__ __forceinline__ Chunk<kBf16, EPL> load_chunk(const void* base, size_t elem_off, bool valid) {
+    Chunk<kBf16, EPL> c;
     if constexpr (kBf16) {
         const uint16_t* p = static_cast<const uint16_t*>(base) + elem_off;
         if constexpr (EPL == 8) {
-            uint4 raw = valid ? *reinterpret_cast<const uint4*>(p) : make_uint4(0, 0, 0, 0);
-            out[0] = bf16_lo(raw.x); out[1] = bf16_hi(raw.x);
-            out[2] = bf16_lo(raw.y); out[3] = bf16_hi(raw.y);
-            out[4] = bf16_lo(raw.z); out[5] = bf16_hi(raw.z);
-            out[6] = bf16_lo(raw.w); out[7] = bf16_hi(raw.w);
+            const uint4 raw = valid ? *reinterpret_cast<const uint4*>(p) : make_uint4(0, 0, 0, 0);
+            c.w[0] = raw.x; c.w[1] = raw.y; c.w[2] = raw.z; c.w[3] = raw.w;
         } else {
-            uint2 raw = valid ? *reinterpret_cast<const uint2*>(p) : make_uint2(0, 0);
-            out[0] = bf16_lo(raw.x); out[1] = bf16_hi(raw.x);
-            out[2] = bf16_lo(raw.y); out[3] = bf16_hi(raw.y);
+            const uint2 raw = valid ? *reinterpret_cast<const uint2*>(p) : make_uint2(0, 0);
+            c.w[0] = raw.x; c.w[1] = raw.y;
         }
     } else {
         const float* p = static_cast<const float*>(base) + elem_off;
 #pragma unroll
         for (int x = 0; x < EPL; x += 4) {
-            float4 raw = valid ? *reinterpret_cast<const float4*>(p + x) : make_float4(0.f, 0.f, 0.f, 0.f);
-            out[x] = raw.x; out[x + 1] = raw.y; out[x + 2] = raw.z; out[x + 3] = raw.w;
+            const float4 raw = valid ? *reinterpret_cast<const float4*>(p + x) : make_float4(0.f, 0.f, 0.f, 0.f);
+            c.f[x] = raw.x; c.f[x + 1] = raw.y; c.f[x + 2] = raw.z; c.f[x + 3] = raw.w;
         }
     }
+    return c;
+}
+
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float acc) {
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a), __builtin_bit_cast(bf16x2, b), acc, false);
 }
 
 template <bool kPrecise>
@@ -50,24 +70,77 @@ __device__ __forceinline__ float exp2_of(float x) {
     else return __builtin_amdgcn_exp2f(x);
 }
 
-template <bool kBf16, int D, int RHO>
+// exp2((a - b) * c) with the convention that an empty stream (a = -inf) weighs 0 even when b = -inf
+template <bool kPrecise>
+__device__ __forceinline__ float rel_weight(float a, float b, float c) {
+    return a == -INFINITY ? 0.f : exp2_of<kPrecise>((a - b) * c);
+}
+
+
+// ---- transposing reduction over a row of 16 lanes -------------------------------------------
+// Each lane brings 16 partial sums; afterwards lane i of the row holds the total of value i.
+// Four pairing steps (mirror, half mirror, quad xor 2, quad xor 1); at each step a lane keeps
+// the half of its values selected by one bit of its index and hands the other half over.
+template <int kCtrl, int N>
+__device__ __forceinline__ void halve(const float (&in)[2 * N], float (&out)[N], bool upper) {
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+        const float keep = upper ? in[k + N] : in[k];
+        const float send = upper ? in[k] : in[k + N];
+        out[k] = keep + dpp_move<kCtrl>(send);
+    }
+}
+
+__device__ __forceinline__ float row16_reduce_scatter(const float (&v)[16], int sub) {
+    float w8[8], w4[4], w2[2], w1[1];
+    halve<0x140, 8>(v, w8, (sub & 8) != 0);    // row_mirror
+    halve<0x141, 4>(w8, w4, (sub & 4) != 0);   // row_half_mirror
+    halve<0x4E, 2>(w4, w2, (sub & 2) != 0);    // quad_perm [2,3,0,1]
+    halve<0xB1, 1>(w2, w1, (sub & 1) != 0);    // quad_perm [1,0,3,2]
+    return w1[0];
+}
+
+// value of lane (4*quad + offset) of the caller's 16-lane row, for every lane of the row
+template <int kSrcInRow>
+__device__ __forceinline__ float row16_broadcast(float x) {
+    // bit-mask swizzle inside each half wave: lane' = (lane & 0x10) | kSrcInRow
+    constexpr int kPattern = (kSrcInRow << 5) | 0x10;
+    return __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(x), kPattern));
+}
+template <int kSrcInRow>
+__device__ __forceinline__ uint32_t row16_broadcast_u32(uint32_t x) {
+    constexpr int kPattern = (kSrcInRow << 5) | 0x10;
+    return static_cast<uint32_t>(__builtin_amdgcn_ds_swizzle(static_cast<int>(x), kPattern));
+}
+
+template <bool kBf16, int D, int RHO, int WPI>
 __global__ __launch_bounds__(kStreamThreads) void stream_attention_kernel(
-    const Item* __restrict__ items, const void* __restrict__ q_, const void* __restrict__ k_,
+    const Item* __restrict__ items, int n_items, const void* __restrict__ q_, const void* __restrict__ k_,
     const void* __restrict__ v_, float* __restrict__ o_part, float* __restrict__ lse_part, float* __restrict__ ws_o,
     float* __restrict__ ws_lse, int n_q_heads, int n_kv_heads, float scale) {
     constexpr int EPL = D / 16;
     constexpr bool kPrecise = !kBf16;
-    __shared__ float sm_m[kStreams][RHO];
-    __shared__ float sm_l[kStreams][RHO];
-    __shared__ float sm_acc[kStreams][RHO][D];
+    constexpr int kItemsPerBlock = kWavesPerBlock / WPI;
+    constexpr int kStreams = 4 * WPI;                  // 16-lane streams per item
+    constexpr int kRowsPerIter = kStreams * kRowsPerStep;
+    __shared__ float sm_m[kItemsPerBlock][WPI][RHO];
+    __shared__ float sm_l[kItemsPerBlock][WPI][RHO];
+    __shared__ float sm_acc[kItemsPerBlock][WPI][RHO][D];
 
-    const Item it = items[blockIdx.x];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
+    const int wave = tid >> 6;
     const int sub = lane & 15;
-    const int stream = (tid >> 6) * 4 + (lane >> 4);
+    const int item_in_block = wave / WPI;
+    const int sw = wave % WPI;
+    const int stream = sw * 4 + (lane >> 4);
+    const int item_idx = blockIdx.x * kItemsPerBlock + item_in_block;
+    const bool item_ok = item_idx < n_items;
+    Item it = items[item_ok ? item_idx : 0];
     const int head0 = it.kv_head * RHO;
-    const float sc2 = scale * kLog2e;
+    const float c2 = scale * kLog2e;
+    // a streaming item is one query row: it sees min(KV_LEN, VIS0) rows of its range
+    const int kv_len = item_ok ? (it.kv_len < it.vis0 ? it.kv_len : it.vis0) : 0;
 
     float* dst_o;
     float* dst_l;
@@ -78,17 +151,11 @@ __global__ __launch_bounds__(kStreamThreads) void stream_attention_kernel(
         dst_o = o_part + (static_cast<size_t>(it.q_row0) * n_q_heads + head0) * D;
         dst_l = lse_part + static_cast<size_t>(it.q_row0) * n_q_heads + head0;
     }
-    const int kv_len = it.kv_len < it.vis0 ? it.kv_len : it.vis0;   // single row: sees min(KV_LEN, VIS0)
-    if (kv_len <= 0) {
-        for (int idx = tid; idx < RHO * D; idx += kStreamThreads) dst_o[idx] = 0.f;
-        if (tid < RHO) dst_l[tid] = -INFINITY;
-        return;
-    }
 
-    float qf[RHO][EPL];
+    Chunk<kBf16, EPL> qc[RHO];
 #pragma unroll
     for (int e = 0; e < RHO; ++e)
-        load_chunk<kBf16, EPL>(q_, (static_cast<size_t>(it.q_row0) * n_q_heads + head0 + e) * D + sub * EPL, true, qf[e]);
+        qc[e] = load_chunk<kBf16, EPL>(q_, (static_cast<size_t>(it.q_row0) * n_q_heads + head0 + e) * D + sub * EPL, true);
 
     float m[RHO], l[RHO], acc[RHO][EPL];
 #pragma unroll
@@ -99,116 +166,284 @@ __global__ __launch_bounds__(kStreamThreads) void stream_attention_kernel(
         for (int x = 0; x < EPL; ++x) acc[e][x] = 0.f;
     }
 
+    // Fast path (bf16, heads in groups of 4): after a transposing reduction lane i of a 16-lane
+    // row owns the score of (head i / 4, row i % 4) of the step, so the softmax is evaluated once
+    // per score instead of once per lane; mq / lq are the running max / sum of head
+    // 4 * hg + sub / 4, replicated over the quad.
+    constexpr bool kFast = kBf16 && (RHO % 4 == 0) && kRowsPerStep == 4;
+    constexpr int kHG = kFast ? RHO / 4 : 1;
+    float mq[kHG], lq[kHG];
+#pragma unroll
+    for (int hg = 0; hg < kHG; ++hg) {
+        mq[hg] = -INFINITY;
+        lq[hg] = 0.f;
+    }
+
     const size_t row_stride = static_cast<size_t>(n_kv_heads) * D;
     const size_t kv_base = (static_cast<size_t>(it.kv_row0) * n_kv_heads + it.kv_head) * D + sub * EPL;
 
-    for (int base = stream; base < kv_len; base += kStreams * kRowsPerStep) {
-        float kf[kRowsPerStep][EPL], vf[kRowsPerStep][EPL];
-        bool valid[kRowsPerStep];
+    Chunk<kBf16, EPL> kc[kRowsPerStep], vc[kRowsPerStep], kn[kRowsPerStep], vn[kRowsPerStep];
+    auto fetch = [&](int base, Chunk<kBf16, EPL>(&kk)[kRowsPerStep], Chunk<kBf16, EPL>(&vv)[kRowsPerStep]) {
 #pragma unroll
         for (int u = 0; u < kRowsPerStep; ++u) {
             const int row = base + u * kStreams;
-            valid[u] = row < kv_len;
+            const bool ok = row < kv_len;
             const size_t off = kv_base + static_cast<size_t>(row) * row_stride;
-            load_chunk<kBf16, EPL>(k_, off, valid[u], kf[u]);
-            load_chunk<kBf16, EPL>(v_, off, valid[u], vf[u]);
+            kk[u] = load_chunk<kBf16, EPL>(k_, off, ok);
+            vv[u] = load_chunk<kBf16, EPL>(v_, off, ok);
         }
-        float s[kRowsPerStep][RHO];
+    };
+    if (stream < kv_len) fetch(stream, kc, vc);
+
+    for (int base = stream; base < kv_len; base += kRowsPerIter) {
+        const int next = base + kRowsPerIter;
+        if (next < kv_len) fetch(next, kn, vn);
+
+        if constexpr (kFast) {
+#pragma unroll
+            for (int hg = 0; hg < kHG; ++hg) {
+                float part[16];
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        float a = 0.f;
+#pragma unroll
+                        for (int x = 0; x < EPL / 2; ++x) a = dot2_bf16(kc[u].w[x], qc[hg * 4 + e].w[x], a);
+                        part[e * 4 + u] = a;
+                    }
+                float sc = row16_reduce_scatter(part, sub);          // score of (head sub / 4, row sub % 4)
+                if (base + (sub & 3) * kStreams >= kv_len) sc = -INFINITY;
+                float mxq = fmaxf(sc, dpp_move<0xB1>(sc));
+                mxq = fmaxf(mxq, dpp_move<0x4E>(mxq));
+                const float m_new = fmaxf(mq[hg], mxq);               // finite: row `base` is valid
+                const float alpha_q = __builtin_amdgcn_exp2f((mq[hg] - m_new) * c2);
+                const float p = __builtin_amdgcn_exp2f(fmaf(sc, c2, -m_new * c2));
+                float ps = p + dpp_move<0xB1>(p);
+                ps += dpp_move<0x4E>(ps);
+                lq[hg] = lq[hg] * alpha_q + ps;
+                mq[hg] = m_new;
+                // rows (0,1) packed in the quad's lane 0, rows (2,3) in its lane 2
+                const bf16x2 pkv = {static_cast<__bf16>(p), static_cast<__bf16>(dpp_move<0xB1>(p))};
+                const uint32_t pk = __builtin_bit_cast(uint32_t, pkv);
+                auto head = [&](auto ec) {
+                    constexpr int e = decltype(ec)::value;
+                    const uint32_t p01 = row16_broadcast_u32<4 * e>(pk);
+                    const uint32_t p23 = row16_broadcast_u32<4 * e + 2>(pk);
+                    const float alpha = row16_broadcast<4 * e>(alpha_q);
+                    float(&a)[EPL] = acc[hg * 4 + e];
+#pragma unroll
+                    for (int x = 0; x < EPL / 2; ++x) {
+                        const uint32_t lo01 = __builtin_amdgcn_perm(vc[1].w[x], vc[0].w[x], 0x05040100u);
+                        const uint32_t hi01 = __builtin_amdgcn_perm(vc[1].w[x], vc[0].w[x], 0x07060302u);
+                        const uint32_t lo23 = __builtin_amdgcn_perm(vc[3].w[x], vc[2].w[x], 0x05040100u);
+                        const uint32_t hi23 = __builtin_amdgcn_perm(vc[3].w[x], vc[2].w[x], 0x07060302u);
+                        a[2 * x] = dot2_bf16(lo23, p23, dot2_bf16(lo01, p01, a[2 * x] * alpha));
+                        a[2 * x + 1] = dot2_bf16(hi23, p23, dot2_bf16(hi01, p01, a[2 * x + 1] * alpha));
+                    }
+                };
+                head(std::integral_constant<int, 0>{});
+                head(std::integral_constant<int, 1>{});
+                head(std::integral_constant<int, 2>{});
+                head(std::integral_constant<int, 3>{});
+            }
+        } else {
+            float s[kRowsPerStep][RHO];
+    #pragma unroll
+            for (int u = 0; u < kRowsPerStep; ++u) {
+    #pragma unroll
+                for (int e = 0; e < RHO; ++e) {
+                    float part = 0.f;
+                    if constexpr (kBf16) {
+    #pragma unroll
+                        for (int x = 0; x < EPL / 2; ++x) part = dot2_bf16(kc[u].w[x], qc[e].w[x], part);
+                    } else {
+    #pragma unroll
+                        for (int x = 0; x < EPL; ++x) part = fmaf(qc[e].f[x], kc[u].f[x], part);
+                    }
+                    s[u][e] = row16_sum(part);
+                }
+            }
+            // rows past the end exist only in the last iteration of a stream
+            if (base + (kRowsPerStep - 1) * kStreams >= kv_len) {
+    #pragma unroll
+                for (int u = 1; u < kRowsPerStep; ++u)
+                    if (base + u * kStreams >= kv_len) {
+    #pragma unroll
+                        for (int e = 0; e < RHO; ++e) s[u][e] = -INFINITY;
+                    }
+            }
+    #pragma unroll
+            for (int e = 0; e < RHO; ++e) {
+                float mx = m[e];
+    #pragma unroll
+                for (int u = 0; u < kRowsPerStep; ++u) mx = fmaxf(mx, s[u][e]);
+                // row `base` is valid, so mx is finite; m = -inf gives alpha = 0
+                const float alpha = exp2_of<kPrecise>((m[e] - mx) * c2);
+                const float mc = mx * c2;
+                float p[kRowsPerStep];
+                float psum = 0.f;
+    #pragma unroll
+                for (int u = 0; u < kRowsPerStep; ++u) {
+                    p[u] = exp2_of<kPrecise>(fmaf(s[u][e], c2, -mc));
+                    psum += p[u];
+                }
+                l[e] = l[e] * alpha + psum;
+                m[e] = mx;
+                if constexpr (kBf16) {
+                    static_assert(kRowsPerStep == 4, "row pairing below assumes 4 rows");
+                    const bf16x2 p01v = {static_cast<__bf16>(p[0]), static_cast<__bf16>(p[1])};
+                    const bf16x2 p23v = {static_cast<__bf16>(p[2]), static_cast<__bf16>(p[3])};
+                    const uint32_t p01 = __builtin_bit_cast(uint32_t, p01v);
+                    const uint32_t p23 = __builtin_bit_cast(uint32_t, p23v);
+    #pragma unroll
+                    for (int x = 0; x < EPL / 2; ++x) {
+                        // the same head-dim element of two rows, side by side
+                        const uint32_t lo01 = __builtin_amdgcn_perm(vc[1].w[x], vc[0].w[x], 0x05040100u);
+                        const uint32_t hi01 = __builtin_amdgcn_perm(vc[1].w[x], vc[0].w[x], 0x07060302u);
+                        const uint32_t lo23 = __builtin_amdgcn_perm(vc[3].w[x], vc[2].w[x], 0x05040100u);
+                        const uint32_t hi23 = __builtin_amdgcn_perm(vc[3].w[x], vc[2].w[x], 0x07060302u);
+                        acc[e][2 * x] = dot2_bf16(lo23, p23, dot2_bf16(lo01, p01, acc[e][2 * x] * alpha));
+                        acc[e][2 * x + 1] = dot2_bf16(hi23, p23, dot2_bf16(hi01, p01, acc[e][2 * x + 1] * alpha));
+                    }
+                } else {
+    #pragma unroll
+                    for (int x = 0; x < EPL; ++x) {
+                        float a = acc[e][x] * alpha;
+    #pragma unroll
+                        for (int u = 0; u < kRowsPerStep; ++u) a = fmaf(p[u], vc[u].f[x], a);
+                        acc[e][x] = a;
+                    }
+                }
+            }
+        }
 #pragma unroll
         for (int u = 0; u < kRowsPerStep; ++u) {
-#pragma unroll
-            for (int e = 0; e < RHO; ++e) {
-                float part = 0.f;
-#pragma unroll
-                for (int x = 0; x < EPL; ++x) part = fmaf(qf[e][x], kf[u][x], part);
-                const float full = row16_sum(part) * sc2;
-                s[u][e] = valid[u] ? full : -INFINITY;
-            }
-        }
-#pragma unroll
-        for (int e = 0; e < RHO; ++e) {
-            float mx = m[e];
-#pragma unroll
-            for (int u = 0; u < kRowsPerStep; ++u) mx = fmaxf(mx, s[u][e]);
-            const float alpha = exp2_of<kPrecise>(m[e] - mx);
-            float p[kRowsPerStep];
-            float psum = 0.f;
-#pragma unroll
-            for (int u = 0; u < kRowsPerStep; ++u) {
-                p[u] = exp2_of<kPrecise>(s[u][e] - mx);
-                psum += p[u];
-            }
-            l[e] = l[e] * alpha + psum;
-            m[e] = mx;
-#pragma unroll
-            for (int x = 0; x < EPL; ++x) {
-                float a = acc[e][x] * alpha;
-#pragma unroll
-                for (int u = 0; u < kRowsPerStep; ++u) a = fmaf(p[u], vf[u][x], a);
-                acc[e][x] = a;
-            }
+            kc[u] = kn[u];
+            vc[u] = vn[u];
         }
     }
 
-    // ---- merge the 16 streams ---------------------------------------------------------------
+    if constexpr (kFast) {
+        // hand every lane of a row the running max / sum of each head
+#pragma unroll
+        for (int hg = 0; hg < kHG; ++hg) {
+            m[hg * 4 + 0] = row16_broadcast<0>(mq[hg]);  l[hg * 4 + 0] = row16_broadcast<0>(lq[hg]);
+            m[hg * 4 + 1] = row16_broadcast<4>(mq[hg]);  l[hg * 4 + 1] = row16_broadcast<4>(lq[hg]);
+            m[hg * 4 + 2] = row16_broadcast<8>(mq[hg]);  l[hg * 4 + 2] = row16_broadcast<8>(lq[hg]);
+            m[hg * 4 + 3] = row16_broadcast<12>(mq[hg]); l[hg * 4 + 3] = row16_broadcast<12>(lq[hg]);
+        }
+    }
+    // ---- merge the four streams of this wavefront (lanes ^16, ^32): scale to the common
+    // maximum, then plain sums ------------------------------------------------------------------
 #pragma unroll
     for (int e = 0; e < RHO; ++e) {
-        if (sub == 0) {
-            sm_m[stream][e] = m[e];
-            sm_l[stream][e] = l[e];
-        }
+        float mw = fmaxf(m[e], __shfl_xor(m[e], 16));
+        mw = fmaxf(mw, __shfl_xor(mw, 32));
+        const float f = rel_weight<kPrecise>(m[e], mw, c2);
+        float lw = l[e] * f;
+        lw += __shfl_xor(lw, 16);
+        lw += __shfl_xor(lw, 32);
+        l[e] = lw;
+        m[e] = mw;
 #pragma unroll
-        for (int x = 0; x < EPL; ++x) sm_acc[stream][e][sub * EPL + x] = acc[e][x];
+        for (int x = 0; x < EPL; ++x) {
+            float a = acc[e][x] * f;
+            a += __shfl_xor(a, 16);
+            a += __shfl_xor(a, 32);
+            acc[e][x] = a;
+        }
     }
-    __syncthreads();
-    for (int idx = tid; idx < RHO * D; idx += kStreamThreads) {
-        const int e = idx / D;
-        const int d = idx - e * D;
-        float top = -INFINITY;
+
+    if constexpr (WPI == 1) {
+        if (item_ok && lane < 16) {
 #pragma unroll
-        for (int s2 = 0; s2 < kStreams; ++s2) top = fmaxf(top, sm_m[s2][e]);
-        float num = 0.f, den = 0.f;
+            for (int e = 0; e < RHO; ++e) {
+                const float inv = l[e] > 0.f ? 1.f / l[e] : 0.f;     // empty range: output 0
 #pragma unroll
-        for (int s2 = 0; s2 < kStreams; ++s2) {
-            const float w = exp2_of<kPrecise>(sm_m[s2][e] - top);   // empty stream: exp2(-inf) = 0
-            num = fmaf(w, sm_acc[s2][e][d], num);
-            den = fmaf(w, sm_l[s2][e], den);
+                for (int x = 0; x < EPL; x += 4)
+                    *reinterpret_cast<float4*>(dst_o + e * D + sub * EPL + x) =
+                        make_float4(acc[e][x] * inv, acc[e][x + 1] * inv, acc[e][x + 2] * inv, acc[e][x + 3] * inv);
+                if (sub == 0) dst_l[e] = l[e] > 0.f ? (m[e] * c2 + log2f(l[e])) * kLn2 : -INFINITY;
+            }
         }
-        dst_o[idx] = num / den;
-        if (d == 0) dst_l[e] = (top + log2f(den)) * kLn2;
+    } else {
+        if (lane < 16) {
+#pragma unroll
+            for (int e = 0; e < RHO; ++e) {
+                if (sub == 0) {
+                    sm_m[item_in_block][sw][e] = m[e];
+                    sm_l[item_in_block][sw][e] = l[e];
+                }
+#pragma unroll
+                for (int x = 0; x < EPL; ++x) sm_acc[item_in_block][sw][e][sub * EPL + x] = acc[e][x];
+            }
+        }
+        __syncthreads();
+        if (item_ok) {
+            const int t_in_item = sw * 64 + lane;
+            for (int idx = t_in_item; idx < RHO * D; idx += 64 * WPI) {
+                const int e = idx / D;
+                const int d = idx - e * D;
+                float top = -INFINITY;
+#pragma unroll
+                for (int w = 0; w < WPI; ++w) top = fmaxf(top, sm_m[item_in_block][w][e]);
+                float num = 0.f, den = 0.f;
+#pragma unroll
+                for (int w = 0; w < WPI; ++w) {
+                    const float wgt = rel_weight<kPrecise>(sm_m[item_in_block][w][e], top, c2);
+                    num = fmaf(wgt, sm_acc[item_in_block][w][e][d], num);
+                    den = fmaf(wgt, sm_l[item_in_block][w][e], den);
+                }
+                dst_o[idx] = den > 0.f ? num / den : 0.f;
+                if (d == 0) dst_l[e] = den > 0.f ? (top * c2 + log2f(den)) * kLn2 : -INFINITY;
+            }
+        }
     }
 }
 
-template <bool kBf16, int D>
-hipError_t launch_rho(const LaunchCtx& c, const Item* items, int32_t n_items, const void* q, const void* k, const void* v,
-                      float* o_part, float* lse_part, float* ws_o, float* ws_lse) {
-    const int rho = c.desc->n_q_heads / c.desc->n_kv_heads;
-    dim3 grid(n_items), block(kStreamThreads);
-#define BLLM_LAUNCH_STREAM(R)                                                                                         \
-    hipLaunchKernelGGL((stream_attention_kernel<kBf16, D, R>), grid, block, 0, c.stream, items, q, k, v, o_part,     \
-                       lse_part, ws_o, ws_lse, c.desc->n_q_heads, c.desc->n_kv_heads, c.scale)
-    switch (rho) {
+template <bool kBf16, int D, int RHO>
+hipError_t launch_wpi(const LaunchCtx& c, const Item* items, int32_t n_items, int wpi, const void* q, const void* k,
+                      const void* v, float* o_part, float* lse_part, float* ws_o, float* ws_lse) {
+    dim3 block(kStreamThreads);
+#define BLLM_LAUNCH_STREAM(W)                                                                                         \
+    hipLaunchKernelGGL((stream_attention_kernel<kBf16, D, RHO, W>), dim3((n_items * W + 3) / 4), block, 0, c.stream,  \
+                       items, n_items, q, k, v, o_part, lse_part, ws_o, ws_lse, c.desc->n_q_heads,                     \
+                       c.desc->n_kv_heads, c.scale)
+    switch (wpi) {
         case 1: BLLM_LAUNCH_STREAM(1); break;
         case 2: BLLM_LAUNCH_STREAM(2); break;
-        case 4: BLLM_LAUNCH_STREAM(4); break;
-        case 8: BLLM_LAUNCH_STREAM(8); break;
-        default: return hipErrorInvalidValue;
+        default: BLLM_LAUNCH_STREAM(4); break;
     }
 #undef BLLM_LAUNCH_STREAM
     return hipGetLastError();
 }
 
+template <bool kBf16, int D>
+hipError_t launch_rho(const LaunchCtx& c, const Item* items, int32_t n_items, int wpi, const void* q, const void* k,
+                      const void* v, float* o_part, float* lse_part, float* ws_o, float* ws_lse) {
+    switch (c.desc->n_q_heads / c.desc->n_kv_heads) {
+        case 1: return launch_wpi<kBf16, D, 1>(c, items, n_items, wpi, q, k, v, o_part, lse_part, ws_o, ws_lse);
+        case 2: return launch_wpi<kBf16, D, 2>(c, items, n_items, wpi, q, k, v, o_part, lse_part, ws_o, ws_lse);
+        case 4: return launch_wpi<kBf16, D, 4>(c, items, n_items, wpi, q, k, v, o_part, lse_part, ws_o, ws_lse);
+        case 8: return launch_wpi<kBf16, D, 8>(c, items, n_items, wpi, q, k, v, o_part, lse_part, ws_o, ws_lse);
+        default: return hipErrorInvalidValue;
+    }
+}
+
 }  // namespace
 
-hipError_t launch_stream_attention(const LaunchCtx& c, const Item* items, int32_t n_items, const void* q, const void* k,
-                                   const void* v, float* o_part, float* lse_part, float* ws_o, float* ws_lse) {
+hipError_t launch_stream_attention(const LaunchCtx& c, const Item* items, int32_t n_items, int waves_per_item,
+                                   const void* q, const void* k, const void* v, float* o_part, float* lse_part,
+                                   float* ws_o, float* ws_lse) {
     if (n_items <= 0) return hipSuccess;
     const bool bf16 = c.desc->dtype == BLLM_BF16;
     const int d = c.desc->head_dim;
-    if (bf16 && d == 128) return launch_rho<true, 128>(c, items, n_items, q, k, v, o_part, lse_part, ws_o, ws_lse);
-    if (bf16 && d == 64) return launch_rho<true, 64>(c, items, n_items, q, k, v, o_part, lse_part, ws_o, ws_lse);
-    if (!bf16 && d == 128) return launch_rho<false, 128>(c, items, n_items, q, k, v, o_part, lse_part, ws_o, ws_lse);
-    if (!bf16 && d == 64) return launch_rho<false, 64>(c, items, n_items, q, k, v, o_part, lse_part, ws_o, ws_lse);
+    const int w = waves_per_item;
+    if (bf16 && d == 128) return launch_rho<true, 128>(c, items, n_items, w, q, k, v, o_part, lse_part, ws_o, ws_lse);
+    if (bf16 && d == 64) return launch_rho<true, 64>(c, items, n_items, w, q, k, v, o_part, lse_part, ws_o, ws_lse);
+    if (!bf16 && d == 128) return launch_rho<false, 128>(c, items, n_items, w, q, k, v, o_part, lse_part, ws_o, ws_lse);
+    if (!bf16 && d == 64) return launch_rho<false, 64>(c, items, n_items, w, q, k, v, o_part, lse_part, ws_o, ws_lse);
     return hipErrorInvalidValue;
 }
 
