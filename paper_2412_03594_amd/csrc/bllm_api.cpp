@@ -256,7 +256,8 @@ static int run_pass(const bllm_prefix_groups* pg, bool prefix, const void* q, co
     hipError_t e;
     if (!tiles.empty()) {
         e = launch_tile_attention(c, prefix ? pg->d.prefix_tile_items : pg->d.suffix_tile_items,
-                                  static_cast<int32_t>(tiles.size()), q, k, v, o_part, lse_part, pg->d.ws_o, pg->d.ws_lse);
+                                  static_cast<int32_t>(tiles.size()), p.tile_waves, q, k, v, o_part, lse_part, pg->d.ws_o,
+                                  pg->d.ws_lse);
         if (e != hipSuccess) return hip_fail(e, "tile attention launch");
     }
     if (!rows.empty()) {

@@ -43,6 +43,8 @@ struct Packing {
     bool prefix_has_split = false, suffix_has_split = false;
     // wavefronts that share one streaming item (1, 2 or 4), per pass
     int32_t prefix_stream_wpi = 4, suffix_stream_wpi = 4;
+    // wavefronts per MFMA tile workgroup (32 stacked query rows each): tile_rows = 32 * tile_waves / rho
+    int32_t tile_waves = 4;
 };
 
 struct DeviceLists {
@@ -87,8 +89,9 @@ struct LaunchCtx {
 hipError_t launch_stream_attention(const LaunchCtx& c, const Item* items, int32_t n_items, int waves_per_item,
                                    const void* q, const void* k, const void* v, float* o_part, float* lse_part,
                                    float* ws_o, float* ws_lse);
-hipError_t launch_tile_attention(const LaunchCtx& c, const Item* items, int32_t n_items, const void* q, const void* k,
-                                 const void* v, float* o_part, float* lse_part, float* ws_o, float* ws_lse);
+hipError_t launch_tile_attention(const LaunchCtx& c, const Item* items, int32_t n_items, int waves, const void* q,
+                                 const void* k, const void* v, float* o_part, float* lse_part, float* ws_o,
+                                 float* ws_lse);
 hipError_t launch_split_combine(const LaunchCtx& c, const RowSplit* row_split, const float* ws_o, const float* ws_lse,
                                 float* o_part, float* lse_part);
 hipError_t launch_lse_merge(const LaunchCtx& c, const float* o_a, const float* lse_a, const float* o_b,

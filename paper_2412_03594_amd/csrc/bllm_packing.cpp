@@ -4,6 +4,7 @@
 // prefill chunks of requests scheduled group by group; Sec. 3.4: per-request
 // metadata separates the shared prefix from the distinct part).
 #include <algorithm>
+#include <cstdlib>
 #include <limits>
 
 #include "bllm_internal.h"
@@ -12,7 +13,7 @@ namespace bllm {
 
 namespace {
 
-constexpr int kTileStackedRows = 256;   // query rows x heads-per-KV-head handled by one MFMA workgroup
+constexpr int kRowsPerWave = 32;         // stacked query rows (token rows x heads per KV head) per wavefront
 constexpr int kKvTile = 64;             // KV rows per MFMA inner step; split lengths are multiples of it
 constexpr int kSplitWhenBelow = 512;    // split the prefix when fewer tile items than this exist
 constexpr int kSplitTargetItems = 1024;
@@ -129,7 +130,8 @@ int build_packing(const bllm_layer_desc& desc, int32_t n_groups, const int32_t* 
 
     // ---- work lists --------------------------------------------------------------------------
     const bool mfma = desc.dtype == BLLM_BF16 && desc.head_dim == 128;
-    p.tile_rows = mfma ? kTileStackedRows / rho : 0;
+    if (const char* ov = std::getenv("BLLM_TUNE_TILE_WAVES")) p.tile_waves = std::atoi(ov) == 8 ? 8 : 4;
+    p.tile_rows = mfma ? kRowsPerWave * p.tile_waves / rho : 0;
     p.prefix_row_split.assign(p.n_rows, RowSplit{0, 0, 0});
     p.suffix_row_split.assign(p.n_rows, RowSplit{0, 0, 0});
 
@@ -231,6 +233,7 @@ int build_packing(const bllm_layer_desc& desc, int32_t n_groups, const int32_t* 
         for (const Item& it : v) total += std::min(it.kv_len, it.vis0);
         const int64_t mean = v.empty() ? 0 : total / static_cast<int64_t>(v.size());
         *wpi = mean >= 192 ? 4 : mean >= 96 ? 2 : 1;
+        if (const char* ov = std::getenv("BLLM_TUNE_STREAM_WPI")) *wpi = std::atoi(ov) == 1 ? 1 : std::atoi(ov) == 2 ? 2 : 4;
     };
     finish_stream_list(p.prefix_row_items, &p.prefix_stream_wpi);
     finish_stream_list(p.suffix_row_items, &p.suffix_stream_wpi);
