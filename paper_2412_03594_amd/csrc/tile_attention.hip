@@ -5,94 +5,94 @@
 // This is the shared-prefix part of prefix-shared attention (BatchLLM
 // Sec. 4.3.3, Sec. 5): because every query of the group sees the same keys, the
 // per-request matrix-vector products become one matrix-matrix product and each
-// KV tile is fetched once per workgroup for up to 256 stacked query rows.  The
+// KV tile is fetched once per workgroup for all its stacked query rows.  The
 // same kernel, with the causal bound of a prefill chunk, serves the chunk rows
 // of the distinct part.
 //
 // Layout of the computation (per wavefront: 32 stacked query rows, 64 KV rows a step):
-//   S^T = K Q^T      A operand = K tile from LDS, B operand = Q held in registers
-//   O^T += V^T P^T   A operand = V^T tile from LDS, B operand = P straight from
-//                    the S^T accumulators
+//   S^T = K Q^T      A operand = K rows from LDS, B operand = Q held in registers
+//   O^T += V^T P^T   A operand = V^T from LDS, B operand = P straight from the
+//                    S^T accumulators
 // Working on the transposes puts one query per lane column, so the running
 // maximum, the running sum and the rescale factor are per-lane scalars.  The
 // reference maximum is raised lazily (only when a tile exceeds it by 2^8), so
 // the common step needs no cross-lane exchange and no rescale of O.
-// The accumulator rows a lane holds (kv = 8i + 4h + j) are not contiguous in kv;
-// the V^T tile is therefore stored in LDS with the kv positions of each group of
-// 16 permuted so that the 8 values a lane needs are one 16-byte read.
-// K and V tiles are double-buffered in LDS; the next tile's global loads are in
-// flight while the current one is multiplied; one barrier per step.
+//
+// Data movement: K and V tiles go from HBM straight into LDS (16-byte
+// direct-to-LDS loads, no register staging), row-major with the 16-byte units
+// of each row XOR-swizzled against bank conflicts; the swizzle is applied on
+// the global side, by choosing which unit a lane fetches.  V is transposed on
+// its way out of LDS by the transposing 64-bit read, which also lets the lanes
+// pick the KV rows in the order the S^T accumulators hold them
+// (kv = 8i + 4h + j).  Tiles are double-buffered; one barrier per step.
+#include <cstdlib>
+
 #include "bllm_device.h"
 #include "bllm_internal.h"
 
 namespace bllm {
 namespace {
 
-constexpr int kBN = 64;              // KV rows per step
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef short short8v __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) short4v* lds_short4_ptr;
+
 constexpr int kD = 128;
-constexpr int kKPitch = 272;         // bytes per K row in LDS (256 + 16 pad: conflict-free 16-byte column reads)
-constexpr int kVtPitch = 128;        // bytes per V^T row in LDS (64 kv slots), XOR-swizzled in 16-byte units
-constexpr int kKBytes = kBN * kKPitch;
-constexpr int kVtBytes = kD * kVtPitch;
+constexpr int kRowBytes = kD * 2;             // one K or V row of one head in LDS
 
-__device__ __forceinline__ int vt_swizzle(int d) { return (d ^ (d >> 3)) & 7; }
-
-// Each thread stages a 4 (kv) x 8 (d) block of K and of V: rows 4*kvq..4*kvq+3,
-// columns 8*dchunk..8*dchunk+7; 16 consecutive threads read one 256-byte row.
-// Rows past the end of the range are staged as zeros.
-__device__ __forceinline__ void stage_global(uint4 (&dst)[4], const uint16_t* __restrict__ src, size_t row_stride,
-                                             int tile_base, int kv_len, int kvq, int dchunk) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int r = tile_base + 4 * kvq + i;
-        dst[i] = (r >= 0 && r < kv_len) ? *reinterpret_cast<const uint4*>(src + static_cast<size_t>(r) * row_stride + dchunk * 8)
-                            : make_uint4(0, 0, 0, 0);
-    }
-}
-
-__device__ __forceinline__ uint32_t comp(const uint4& x, int c) {
-    return c == 0 ? x.x : c == 1 ? x.y : c == 2 ? x.z : x.w;
-}
-
-__device__ __forceinline__ void stage_k_to_lds(const uint4 (&st)[4], unsigned char* sk, int kvq, int dchunk) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) *reinterpret_cast<uint4*>(sk + (4 * kvq + i) * kKPitch + dchunk * 16) = st[i];
-}
-
-// transpose the 4 x 8 block of V: for each column d, the 4 kv values become one 8-byte word
-__device__ __forceinline__ void stage_v_to_lds(const uint4 (&st)[4], unsigned char* svt, int kvq, int dchunk) {
-    const int unit = 2 * (kvq >> 2) + (kvq & 1);
-    const int half8 = (kvq >> 1) & 1;
-#pragma unroll
-    for (int dd = 0; dd < 8; ++dd) {
-        const int c = dd >> 1;
-        uint32_t w0, w1;
-        if ((dd & 1) == 0) {
-            w0 = __builtin_amdgcn_perm(comp(st[1], c), comp(st[0], c), 0x05040100u);
-            w1 = __builtin_amdgcn_perm(comp(st[3], c), comp(st[2], c), 0x05040100u);
-        } else {
-            w0 = __builtin_amdgcn_perm(comp(st[1], c), comp(st[0], c), 0x07060302u);
-            w1 = __builtin_amdgcn_perm(comp(st[3], c), comp(st[2], c), 0x07060302u);
-        }
-        const int d = 8 * dchunk + dd;
-        *reinterpret_cast<uint2*>(svt + d * kVtPitch + ((unit ^ vt_swizzle(d)) << 4) + half8 * 8) = make_uint2(w0, w1);
-    }
-}
+// physical 16-byte unit of logical unit u in LDS row r
+__device__ __forceinline__ int k_unit(int u, int r) { return u ^ (r & 15); }
+__device__ __forceinline__ int v_unit(int u, int r) { return u ^ ((r & 3) << 2); }
 
 // The running maximum is only raised when a tile exceeds it by more than this many powers of
 // two; below that the stale maximum is exact arithmetic anyway (weights up to 2^8, fp32 sums).
 constexpr float kMaxSlack = 8.f;
 
+// gfx950-only instructions live in small device functions whose bodies exist in the device
+// pass only: the host pass cannot type-check these builtins, and a kernel template whose body
+// fails there silently loses its launch stub.
+__device__ __forceinline__ void dma16_to_lds(const unsigned char* gptr, unsigned char* lds_wave_base) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    // every lane moves 16 bytes from its own global address to lds_wave_base + 16 * lane
+    __builtin_amdgcn_global_load_lds(gptr, (lds_void_ptr)lds_wave_base, 16, 0, 0);
+#endif
+}
+
+// s_waitcnt vmcnt(kN) only: wait until at most kN of this wavefront's vector-memory operations
+// (here: direct-to-LDS loads, which complete in order) are still in flight
+template <int kN>
+__device__ __forceinline__ void wait_vector_memory() {
+    static_assert(kN >= 0 && kN < 64, "vmcnt is a 6-bit field");
+#if defined(__HIP_DEVICE_COMPILE__)
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (kN & 15) | ((kN >> 4) << 14));
+#endif
+}
+
+// Transposing 64-bit LDS read of 16-bit elements: inside each group of 16 lanes, lane i receives
+// element i % 4 of the four 8-byte chunks addressed by lanes i / 4, 4 + i / 4, 8 + i / 4, 12 + i / 4.
+__device__ __forceinline__ short4v lds_read_tr16(const unsigned char* lds_addr) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)lds_addr);
+#else
+    return short4v{0, 0, 0, 0};
+#endif
+}
+
 // NW wavefronts per workgroup, 32 stacked query rows each.  With about 200 registers a
 // wavefront, two wavefronts share a SIMD, so one runs its exp / convert work on the vector
-// ALUs while the other keeps the matrix cores busy.
-template <int NW>
+// ALUs while the other keeps the matrix cores busy.  BN KV rows per step; NS tile buffers in
+// LDS, so the loads of a tile are issued NS - 1 steps before it is used.
+template <int NW, int BN, int NS>
 __global__ __launch_bounds__(64 * NW, 2) void tile_attention_kernel(
     const Item* __restrict__ items, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const uint16_t* __restrict__ v, float* __restrict__ o_part, float* __restrict__ lse_part, float* __restrict__ ws_o,
     float* __restrict__ ws_lse, int n_q_heads, int n_kv_heads, int log2_rho, float scale) {
-    __shared__ __attribute__((aligned(16))) unsigned char smem_k[2][kKBytes];
-    __shared__ __attribute__((aligned(16))) unsigned char smem_vt[2][kVtBytes];
+    constexpr int kBN = BN;
+    constexpr int kKvb = BN / 32;                    // 32-row blocks of S^T per step
+    constexpr int kTileBytes = kBN * kRowBytes;
+    constexpr int kBufBytes = 2 * kTileBytes;        // K tile + V tile
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[NS * kBufBytes];   // [buf][K tile | V tile]
 
     const Item it = items[blockIdx.x];
     const int tid = threadIdx.x;
@@ -154,48 +154,92 @@ __global__ __launch_bounds__(64 * NW, 2) void tile_attention_kernel(
     float m_run = -INFINITY;         // reference maximum, in log2 units (score * c2)
     float l_run = 0.f;               // this lane's share of the running sum
 
-    const size_t row_stride = static_cast<size_t>(n_kv_heads) * kD;
-    const uint16_t* kg = k + (static_cast<size_t>(it.kv_row0) * n_kv_heads + it.kv_head) * kD;
-    const uint16_t* vg = v + (static_cast<size_t>(it.kv_row0) * n_kv_heads + it.kv_head) * kD;
+    // ---- HBM -> LDS: a wavefront instruction moves 4 rows (1 KB); a K or V tile is 16 of them.
+    // Instruction j of a tile fills LDS rows 4j .. 4j+3; lane l fills row 4j + l/16, physical
+    // unit l%16, i.e. it fetches the logical unit that the swizzle maps there.
+    constexpr int kInstrPerWave = kBN / 4 / NW;     // per matrix per tile
+    static_assert(kInstrPerWave >= 1, "tile too small for this many wavefronts");
+    const uint32_t row_bytes = static_cast<uint32_t>(n_kv_heads) * kRowBytes;
+    const size_t tile_stride = static_cast<size_t>(row_bytes) * kBN;
+    const unsigned char* kg = reinterpret_cast<const unsigned char*>(k) +
+                              (static_cast<size_t>(it.kv_row0) * n_kv_heads + it.kv_head) * kRowBytes;
+    const unsigned char* vg = reinterpret_cast<const unsigned char*>(v) +
+                              (static_cast<size_t>(it.kv_row0) * n_kv_heads + it.kv_head) * kRowBytes;
     const int n_tiles = (kv_len + kBN - 1) / kBN;
-
-    // Staging: 256 threads cover a 64 x 128 tile in 4 (kv) x 8 (d) blocks.  With 8 wavefronts the
-    // lower four stage K and the upper four stage V; with 4 wavefronts every thread stages both.
-    const int st_tid = tid & 255;
-    const int dchunk = st_tid & 15;
-    const int kvq = st_tid >> 4;
-    const bool do_k = NW == 4 || tid < 256;
-    const bool do_v = NW == 4 || tid >= 256;
-    uint4 st_k[4], st_v[4];
-    auto load_tile = [&](int tile_base) {
-        if (do_k) stage_global(st_k, kg, row_stride, tile_base, kv_len, kvq, dchunk);
-        if (do_v) stage_global(st_v, vg, row_stride, tile_base, kv_len, kvq, dchunk);
+    uint32_t goff_k[kInstrPerWave], goff_v[kInstrPerWave];
+#pragma unroll
+    for (int jj = 0; jj < kInstrPerWave; ++jj) {
+        const int r = 4 * (wave * kInstrPerWave + jj) + (lane >> 4);
+        goff_k[jj] = r * row_bytes + (k_unit(lane & 15, r) << 4);
+        goff_v[jj] = r * row_bytes + (v_unit(lane & 15, r) << 4);
+    }
+    auto dma_tile = [&](int tile, int buf) {
+        const unsigned char* kt = kg + tile * tile_stride;
+        const unsigned char* vt = vg + tile * tile_stride;
+        unsigned char* lds_k = smem + buf * kBufBytes + wave * kInstrPerWave * 1024;
+        unsigned char* lds_v = lds_k + kTileBytes;
+        const int rows_left = kv_len - tile * kBN;
+        if (rows_left >= kBN) {
+#pragma unroll
+            for (int jj = 0; jj < kInstrPerWave; ++jj) {
+                dma16_to_lds(kt + goff_k[jj], lds_k + jj * 1024);
+                dma16_to_lds(vt + goff_v[jj], lds_v + jj * 1024);
+            }
+        } else {
+            // last tile of the range: rows past the end re-read the last row (their scores are masked)
+#pragma unroll
+            for (int jj = 0; jj < kInstrPerWave; ++jj) {
+                const int r = 4 * (wave * kInstrPerWave + jj) + (lane >> 4);
+                const int rc = min(r, rows_left - 1);
+                dma16_to_lds(kt + (rc * row_bytes + (k_unit(lane & 15, r) << 4)), lds_k + jj * 1024);
+                dma16_to_lds(vt + (rc * row_bytes + (v_unit(lane & 15, r) << 4)), lds_v + jj * 1024);
+            }
+        }
     };
-    auto store_tile = [&](int buf) {
-        if (do_k) stage_k_to_lds(st_k, smem_k[buf], kvq, dchunk);
-        if (do_v) stage_v_to_lds(st_v, smem_vt[buf], kvq, dchunk);
-    };
 
-    load_tile(0);
-    store_tile(0);
+    // ---- LDS read addresses ---------------------------------------------------------------------
+    // K (A operand of S^T): lane (row = col, half h) reads unit 2t + h of row 32 kvb + col.
+    uint32_t ka[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) ka[t] = col * kRowBytes + (k_unit(2 * t + h, col) << 4);
+    // V (A operand of O^T) through the transposing read: inside a group of 16 lanes, lane i = 4e + c
+    // addresses the 8 bytes V[row(e)][32 db + 16 g1 + 4c ..+3] and receives V[row(0..3)][32 db + col];
+    // row(e) = 32 kvb + 16 u + 8 a + 4 h + e are the KV rows of accumulator registers 8u + 4a + e.
+    uint32_t va[4];
+    {
+        const int e = (lane >> 2) & 3;
+        const int c = lane & 3;
+        const int g1 = (lane >> 4) & 1;
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+            va[db] = kTileBytes + (4 * h + e) * kRowBytes + (v_unit(4 * db + 2 * g1 + (c >> 1), e) << 4) + (c & 1) * 8;
+    }
+
+    // prologue: tiles 0 .. NS-2 in flight, tile 0 landed
+#pragma unroll
+    for (int pre = 0; pre < NS - 1; ++pre)
+        if (pre < n_tiles) dma_tile(pre, pre);
+    constexpr int kDmaPerTile = 2 * kInstrPerWave;
+    if (n_tiles >= NS - 1) wait_vector_memory<(NS - 2) * kDmaPerTile>();
+    else wait_vector_memory<0>();
     __syncthreads();
 
+    int buf = 0;
     for (int tile = 0; tile < n_tiles; ++tile) {
-        const int buf = tile & 1;
         const int tile_base = tile * kBN;
-        const bool more = tile + 1 < n_tiles;
-        if (more) load_tile(tile_base + kBN);
+        // the buffer of tile - 1 is free: its last readers ran before the previous barrier
+        if (tile + NS - 1 < n_tiles) dma_tile(tile + NS - 1, buf == 0 ? NS - 1 : buf - 1);
+        const unsigned char* sb = smem + buf * kBufBytes;
 
         // ---- S^T = K Q^T (64 kv x 32 queries) ---------------------------------------------------
-        const unsigned char* sk = smem_k[buf];
-        floatx16 sacc[2];
+        floatx16 sacc[kKvb];
         {
             const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int t = 0; t < 8; ++t) {
 #pragma unroll
-                for (int kvb = 0; kvb < 2; ++kvb) {
-                    const uint4 raw = *reinterpret_cast<const uint4*>(sk + (32 * kvb + col) * kKPitch + 32 * t + 16 * h);
+                for (int kvb = 0; kvb < kKvb; ++kvb) {
+                    const uint4 raw = *reinterpret_cast<const uint4*>(sb + ka[t] + kvb * 32 * kRowBytes);
                     sacc[kvb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, raw), qreg[t],
                                                                          t == 0 ? zero : sacc[kvb], 0, 0, 0);
                 }
@@ -203,7 +247,7 @@ __global__ __launch_bounds__(64 * NW, 2) void tile_attention_kernel(
         }
         if (tile_base + kBN > wave_min_vis) {       // last tile(s) of an item: mask what a row cannot see
 #pragma unroll
-            for (int kvb = 0; kvb < 2; ++kvb)
+            for (int kvb = 0; kvb < kKvb; ++kvb)
 #pragma unroll
                 for (int x = 0; x < 16; ++x) {
                     const int kvi = tile_base + 32 * kvb + 8 * (x >> 2) + 4 * h + (x & 3);
@@ -214,7 +258,7 @@ __global__ __launch_bounds__(64 * NW, 2) void tile_attention_kernel(
         // ---- reference maximum: raised (and O, l rescaled) only when exceeded by kMaxSlack ------
         float mx = -INFINITY;
 #pragma unroll
-        for (int kvb = 0; kvb < 2; ++kvb)
+        for (int kvb = 0; kvb < kKvb; ++kvb)
 #pragma unroll
             for (int x = 0; x < 16; ++x) mx = fmaxf(mx, sacc[kvb][x]);
         const float zloc = mx * c2;
@@ -232,10 +276,10 @@ __global__ __launch_bounds__(64 * NW, 2) void tile_attention_kernel(
                 for (int x = 0; x < 16; ++x) oacc[db][x] *= alpha;
         }
         // ---- P = exp2(S c2 - m) in bf16, running sum -------------------------------------------
-        bf16x8 pb[2][2];             // [kvb][u]
+        bf16x8 pb[kKvb][2];          // [kvb][u]
         float lsum = 0.f;
 #pragma unroll
-        for (int kvb = 0; kvb < 2; ++kvb)
+        for (int kvb = 0; kvb < kKvb; ++kvb)
 #pragma unroll
             for (int u = 0; u < 2; ++u)
 #pragma unroll
@@ -246,23 +290,27 @@ __global__ __launch_bounds__(64 * NW, 2) void tile_attention_kernel(
                 }
         l_run += lsum;
         // ---- O^T += V^T P^T ---------------------------------------------------------------------
-        const unsigned char* svt = smem_vt[buf];
 #pragma unroll
-        for (int kvb = 0; kvb < 2; ++kvb) {
+        for (int kvb = 0; kvb < kKvb; ++kvb) {
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
 #pragma unroll
                 for (int db = 0; db < 4; ++db) {
-                    const int d = 32 * db + col;
-                    const int unit = 4 * kvb + 2 * u + h;
-                    const uint4 raw = *reinterpret_cast<const uint4*>(svt + d * kVtPitch + ((unit ^ vt_swizzle(d)) << 4));
-                    oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, raw), pb[kvb][u], oacc[db], 0, 0, 0);
+                    const unsigned char* base = sb + va[db] + (32 * kvb + 16 * u) * kRowBytes;
+                    const short4v lo = lds_read_tr16(base);
+                    const short4v hi = lds_read_tr16(base + 8 * kRowBytes);
+                    const short8v a = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                    oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), pb[kvb][u], oacc[db], 0, 0, 0);
                 }
             }
         }
-        // the other buffers were last read in the previous step, before its barrier
-        if (more) store_tile(buf ^ 1);
+        // Own loads of the next tile have landed (the NS - 2 tiles after it may still be in
+        // flight; near the end of the range fewer were issued, so wait for everything); after
+        // the barrier everybody's have landed, and everybody is done reading this tile.
+        if (tile + NS - 1 < n_tiles) wait_vector_memory<(NS - 2) * kDmaPerTile>();
+        else wait_vector_memory<0>();
         __syncthreads();
+        buf = buf + 1 == NS ? 0 : buf + 1;
     }
 
     // ---- epilogue: normalise and store O (transposed back), log-sum-exp --------------------------
@@ -295,12 +343,22 @@ hipError_t launch_tile_attention(const LaunchCtx& c, const Item* items, int32_t 
     const uint16_t* qq = static_cast<const uint16_t*>(q);
     const uint16_t* kk = static_cast<const uint16_t*>(k);
     const uint16_t* vv = static_cast<const uint16_t*>(v);
-    if (waves == 8)
-        hipLaunchKernelGGL(tile_attention_kernel<8>, dim3(n_items), dim3(512), 0, c.stream, items, qq, kk, vv, o_part,
-                           lse_part, ws_o, ws_lse, c.desc->n_q_heads, c.desc->n_kv_heads, log2_rho, c.scale);
-    else
-        hipLaunchKernelGGL(tile_attention_kernel<4>, dim3(n_items), dim3(256), 0, c.stream, items, qq, kk, vv, o_part,
-                           lse_part, ws_o, ws_lse, c.desc->n_q_heads, c.desc->n_kv_heads, log2_rho, c.scale);
+#define BLLM_LAUNCH_TILE(NW_, BN_, NS_)                                                                              \
+    hipLaunchKernelGGL((tile_attention_kernel<NW_, BN_, NS_>), dim3(n_items), dim3(64 * NW_), 0, c.stream, items, qq, kk, \
+                       vv, o_part, lse_part, ws_o, ws_lse, c.desc->n_q_heads, c.desc->n_kv_heads, log2_rho, c.scale)
+    const char* ov = std::getenv("BLLM_TUNE_TILE_SHAPE");
+    const int shape = ov ? std::atoi(ov) : 0;
+    if (waves == 8) {
+        if (shape == 1) BLLM_LAUNCH_TILE(8, 64, 4);
+        else if (shape == 2) BLLM_LAUNCH_TILE(8, 64, 2);
+        else BLLM_LAUNCH_TILE(8, 64, 3);
+    } else {
+        if (shape == 1) BLLM_LAUNCH_TILE(4, 32, 4);
+        else if (shape == 2) BLLM_LAUNCH_TILE(4, 32, 5);
+        else if (shape == 3) BLLM_LAUNCH_TILE(4, 32, 3);
+        else BLLM_LAUNCH_TILE(4, 64, 2);
+    }
+#undef BLLM_LAUNCH_TILE
     return hipGetLastError();
 }
 
