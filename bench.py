@@ -23,6 +23,13 @@ import numpy as np
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 
+# HBM bytes per launch of each pass, from rocprofv3 FETCH_SIZE + WRITE_SIZE runs scaled by a plain
+# copy of known size (the summaries and commands are under profiles/<workload>_kernels.md).
+MEASURED_TRAFFIC_BYTES = {
+    "l8b_decode": {"suffix": 306.5e6, "prefix": 146.2e6, "merge": 10.8e6},
+    "rank_longprefix": {"suffix": 331.6e6, "prefix": 299.0e6, "merge": 43.0e6},
+}
+
 
 def algorithmic_work(batch, meta):
     """Bytes / flops the method must move per step (not what it avoids)."""
@@ -66,7 +73,7 @@ def oracle_baseline(batch, vals, budget_s=15.0):
     """Time the CPU oracle (as it stands, single process) on a bounded stratified
     sample of requests: one active request per group, round robin, until the budget is used."""
     from oracle import attention as oa
-    from threadpoolctl import threadpool_info
+    from threadpoolctl import threadpool_limits
     L = batch.layer
     by_group = {}
     for r in range(batch.n_requests):
@@ -81,18 +88,20 @@ def oracle_baseline(batch, vals, budget_s=15.0):
         order += layer
         depth += 1
     done_rows, done_reqs = 0, 0
-    t0 = time.perf_counter()
-    for r in order:
-        oa.prefix_shared_attention(vals["q"], vals["k_prefix"], vals["v_prefix"], vals["k_suffix"], vals["v_suffix"],
-                                   batch.prefix_len, batch.req_group, batch.req_suffix_len, batch.req_q_len,
-                                   L.n_q_heads, L.n_kv_heads, requests=[r], parts=False)
-        done_rows += int(batch.req_q_len[r])
-        done_reqs += 1
-        if time.perf_counter() - t0 > budget_s:
-            break
-    dt = time.perf_counter() - t0
-    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-    return {"value": done_rows / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+    # the oracle is plain single-process numpy; its BLAS calls are pinned to one thread so that
+    # "cores" is what it really used
+    with threadpool_limits(limits=1):
+        t0 = time.perf_counter()
+        for r in order:
+            oa.prefix_shared_attention(vals["q"], vals["k_prefix"], vals["v_prefix"], vals["k_suffix"],
+                                       vals["v_suffix"], batch.prefix_len, batch.req_group, batch.req_suffix_len,
+                                       batch.req_q_len, L.n_q_heads, L.n_kv_heads, requests=[r], parts=False)
+            done_rows += int(batch.req_q_len[r])
+            done_reqs += 1
+            if time.perf_counter() - t0 > budget_s:
+                break
+        dt = time.perf_counter() - t0
+    return {"value": round(done_rows / dt, 3), "unit": "tokens/s", "cores": 1, "kind": "oracle",
             "sample": "%d of %d active requests (round robin over the %d groups), %d rows, %.1f s" %
                       (done_reqs, len(order), len(by_group), done_rows, dt)}
 
@@ -180,6 +189,7 @@ def roofline_of(res):
     """Roofline record of the pass that takes the most time."""
     t = res["t_pass"]
     name = max(("prefix", "suffix", "merge"), key=lambda k: t[k])
+    traffic = MEASURED_TRAFFIC_BYTES.get(res["batch"].name, {}).get(name)
     w = res["work"][name]
     sec = t[name] * 1e-3
     # arithmetic intensity decides which roof bounds the pass
@@ -187,12 +197,12 @@ def roofline_of(res):
     if name == "prefix" and ai > PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9):
         a = w["flops"] / sec / 1e12
         return {"kernel": "tile_attention_kernel (shared-prefix pass)", "bound": "mfma", "achieved": round(a, 2),
-                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(a / PEAK_BF16_TFLOPS, 4), "traffic": None}
+                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(a / PEAK_BF16_TFLOPS, 4), "traffic": traffic}
     a = w["bytes"] / sec / 1e9
     kern = {"prefix": "tile_attention_kernel (shared-prefix pass)",
             "suffix": "stream_attention_kernel (distinct-suffix pass)", "merge": "lse_merge_kernel"}[name]
     return {"kernel": kern, "bound": "hbm", "achieved": round(a, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-            "frac": round(a / PEAK_HBM_GBS, 4), "traffic": None}
+            "frac": round(a / PEAK_HBM_GBS, 4), "traffic": traffic}
 
 
 def main():
@@ -206,6 +216,8 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--rotate", type=int, default=2, help="copies of the KV tensors cycled through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 256 MiB device-to-device copy (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (no sharding or collectives are part of it); "
@@ -219,6 +231,12 @@ def main():
         print("bench.py: no GPU visible; the hot path has no CPU fallback", file=sys.stderr)
         sys.exit(3)
     bllm.load_library()
+    if args.calibrate_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
 
     main_res = run_workload(args.workload, args.steps, args.warmup, args.seed, args.rotate, torch, bllm, workload)
     batch = main_res["batch"]

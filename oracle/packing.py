@@ -13,7 +13,8 @@ code so the two can be compared bit for bit:
   * row i of a request with suffix length s and q rows sits at suffix
     position s - q + i.
 
-All arrays are int32.
+build_work_lists re-derives, by the documented rules, the work lists the kernels
+consume (tile items, streaming items, split tables).  All arrays are int32.
 """
 import numpy as np
 
@@ -78,4 +79,113 @@ def pack_token_batch(prefix_len, req_group, req_suffix_len, req_q_len):
         "row_req": i32(row_req),
         "row_pos": i32(row_pos),
         "row_src": i32(row_src),
+    }
+
+
+# ---------------------------------------------------------------- work lists ----
+# Field order of an item (8 int32): first packed row, token rows, KV head, first KV row,
+# KV rows in range, KV rows of the range visible to the first row (row i sees
+# min(range, visible + i)), workspace row of the first row (-1: written directly), 0.
+ITEM_INTS = 8
+
+SPLIT_WHEN_BELOW = 512      # split prefixes when fewer tile items than this would exist
+SPLIT_TARGET_ITEMS = 1024
+MIN_SPLIT_LEN = 256
+KV_TILE = 64
+
+
+def _ceil_div(a, b):
+    return (a + b - 1) // b
+
+
+def build_work_lists(meta, prefix_len, req_suffix_len, req_q_len, n_q_heads, n_kv_heads, head_dim,
+                     is_bf16, tile_rows):
+    """Work lists the kernels consume, rebuilt from the packing arrays by the documented
+    rules.  tile_rows is taken from the library's view (token rows per matrix-core tile:
+    32 * wavefronts per workgroup / (Hq/Hkv); 0 when the dtype / head_dim has no matrix-core
+    path and every row streams)."""
+    prefix_len = [int(x) for x in prefix_len]
+    s_len = [int(x) for x in req_suffix_len]
+    q_len = [int(x) for x in req_q_len]
+    G = len(prefix_len)
+    T = int(meta["n_rows"])
+    grs = [int(x) for x in meta["group_row_start"]]
+    pks = [int(x) for x in meta["prefix_kv_start"]]
+    rks = [int(x) for x in meta["req_kv_start"]]
+    rrs = [int(x) for x in meta["req_row_start"]]
+    perm = [int(x) for x in meta["perm_req"]]
+    row_req = [int(x) for x in meta["row_req"]]
+    row_pos = [int(x) for x in meta["row_pos"]]
+    mfma = bool(is_bf16) and head_dim == 128
+    assert (tile_rows > 0) == mfma
+
+    prefix_tiles, prefix_rows, suffix_tiles, suffix_rows = [], [], [], []
+    prefix_row_split = [[0, 0, 0] for _ in range(T)]
+    suffix_row_split = [[0, 0, 0] for _ in range(T)]
+    split_len = 0
+    ws_rows = 0
+    if mfma:
+        br = tile_rows
+        base_items, max_lp = 0, 0
+        for g in range(G):
+            rows = grs[g + 1] - grs[g]
+            if rows == 0 or prefix_len[g] == 0:
+                continue
+            base_items += _ceil_div(rows, br) * n_kv_heads
+            max_lp = max(max_lp, prefix_len[g])
+        if 0 < base_items < SPLIT_WHEN_BELOW:
+            want = _ceil_div(SPLIT_TARGET_ITEMS, base_items)
+            ln = _ceil_div(_ceil_div(max_lp, want), KV_TILE) * KV_TILE
+            ln = max(ln, MIN_SPLIT_LEN)
+            if ln < max_lp:
+                split_len = ln
+        for g in range(G):
+            row0 = grs[g]
+            rows = grs[g + 1] - row0
+            if rows == 0:
+                continue
+            lp = prefix_len[g]
+            n_sp = _ceil_div(lp, split_len) if (split_len > 0 and lp > split_len) else 1
+            ws_base = ws_rows
+            if n_sp > 1:
+                ws_rows += rows * n_sp
+                for i in range(rows):
+                    prefix_row_split[row0 + i] = [ws_base + i, rows, n_sp]
+            for c in range(n_sp):
+                kv_off = c * split_len if n_sp > 1 else 0
+                kv_len = min(split_len, lp - kv_off) if n_sp > 1 else lp
+                for i0 in range(0, rows, br):
+                    for j in range(n_kv_heads):
+                        prefix_tiles.append([row0 + i0, min(br, rows - i0), j, pks[g] + kv_off, kv_len, kv_len,
+                                             (ws_base + c * rows + i0) if n_sp > 1 else -1, 0])
+        for a, r in enumerate(perm):
+            nq, s, row0 = q_len[r], s_len[r], rrs[a]
+            if nq == 1:
+                for j in range(n_kv_heads):
+                    suffix_rows.append([row0, 1, j, rks[r], s, s, -1, 0])
+            else:
+                for i0 in range(0, nq, br):
+                    n = min(br, nq - i0)
+                    for j in range(n_kv_heads):
+                        suffix_tiles.append([row0 + i0, n, j, rks[r], s - nq + i0 + n, s - nq + i0 + 1, -1, 0])
+    else:
+        for g in range(G):
+            for t in range(grs[g], grs[g + 1]):
+                for j in range(n_kv_heads):
+                    prefix_rows.append([t, 1, j, pks[g], prefix_len[g], prefix_len[g], -1, 0])
+        for t in range(T):
+            for j in range(n_kv_heads):
+                suffix_rows.append([t, 1, j, rks[row_req[t]], row_pos[t] + 1, row_pos[t] + 1, -1, 0])
+    # streaming items: longest range first (stable)
+    key = lambda it: -min(it[4], it[5])
+    prefix_rows.sort(key=key)
+    suffix_rows.sort(key=key)
+
+    arr = lambda x, w: np.asarray(x, dtype=np.int32).reshape(-1, w)
+    return {
+        "prefix_tile_items": arr(prefix_tiles, ITEM_INTS), "prefix_row_items": arr(prefix_rows, ITEM_INTS),
+        "suffix_tile_items": arr(suffix_tiles, ITEM_INTS), "suffix_row_items": arr(suffix_rows, ITEM_INTS),
+        "prefix_row_split": arr(prefix_row_split, 3), "suffix_row_split": arr(suffix_row_split, 3),
+        "prefix_split_len": split_len, "suffix_split_len": 0,
+        "n_prefix_ws_rows": ws_rows, "n_suffix_ws_rows": 0,
     }

@@ -92,3 +92,56 @@ def test_host_only_handle_refuses_device_calls():
         bllm.lse_merge(pg, 1, 1, 1, 1, 1, None, stream=0)
     assert e.value.code == -1
     pg.destroy()
+
+
+WORK_KEYS = ["prefix_tile_items", "prefix_row_items", "suffix_tile_items", "suffix_row_items", "prefix_row_split",
+             "suffix_row_split", "prefix_split_len", "suffix_split_len", "n_prefix_ws_rows", "n_suffix_ws_rows"]
+
+
+def check_work_lists(b):
+    from oracle.packing import build_work_lists
+    L = b.layer
+    m = host_pack(b).metadata()
+    ref_meta = pack_token_batch(b.prefix_len, b.req_group, b.req_suffix_len, b.req_q_len)
+    ref = build_work_lists(ref_meta, b.prefix_len, b.req_suffix_len, b.req_q_len, L.n_q_heads, L.n_kv_heads,
+                           L.head_dim, L.dtype == workload.BF16, m["tile_rows"])
+    for k in WORK_KEYS:
+        assert np.array_equal(np.asarray(m[k]), np.asarray(ref[k])), k
+    return m
+
+
+@pytest.mark.parametrize("name", ["tiny_fp32", "l8b_decode", "l8b_mixed", "rank_longprefix", "l70b_zipf_32k"])
+def test_work_lists_bit_exact_on_configs(name):
+    m = check_work_lists(workload.CONFIGS[name](2, True))
+    if name == "rank_longprefix":
+        assert m["prefix_split_len"] > 0 and m["n_prefix_ws_rows"] > 0       # few, long groups are split
+    if name == "l8b_mixed":
+        assert m["prefix_split_len"] == 0                                    # enough tiles without splitting
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_work_lists_bit_exact_ragged(seed):
+    check_work_lists(workload.ragged_toy(seed, dtype=workload.BF16, n_q_heads=8, n_kv_heads=2, head_dim=128,
+                                         n_groups=4, max_prefix=700, max_group=6, max_suffix=200, max_chunk=150))
+    check_work_lists(workload.ragged_toy(seed, n_q_heads=4, n_kv_heads=2, head_dim=64))
+
+
+def test_work_items_cover_every_row_head_once():
+    """Every (packed row, KV head) is produced by exactly one item per split, the KV ranges of a
+    row's splits tile its prefix, and causal bounds match row_pos."""
+    b = workload.l8b_mixed(0)
+    b.prefix_len[:] = np.minimum(b.prefix_len, 900)
+    m = host_pack(b).metadata()
+    T, H = m["n_rows"], b.layer.n_kv_heads
+    cover = np.zeros((T, H), dtype=np.int64)
+    for it in m["prefix_tile_items"]:
+        cover[it[0]:it[0] + it[1], it[2]] += it[4]
+    row_group = b.req_group[m["row_req"]]
+    assert np.array_equal(cover, np.repeat(b.prefix_len[row_group][:, None], H, axis=1))
+    seen = np.zeros((T, H), dtype=np.int64)
+    for it in list(m["suffix_tile_items"]) + list(m["suffix_row_items"]):
+        for i in range(it[1]):
+            t = it[0] + i
+            assert min(it[4], it[5] + i) == m["row_pos"][t] + 1
+            seen[t, it[2]] += 1
+    assert np.all(seen == 1)
