@@ -43,8 +43,11 @@ __device__ __forceinline__ Chunk<kBf16, EPL> load_chunk(const void* base, size_t
     if constexpr (kBf16) {
         const uint16_t* p = static_cast<const uint16_t*>(base) + elem_off;
         if constexpr (EPL == 8) {
-            const uint4 raw = valid ? *reinterpret_cast<const uint4*>(p) : make_uint4(0, 0, 0, 0);
-            c.w[0] = raw.x; c.w[1] = raw.y; c.w[2] = raw.z; c.w[3] = raw.w;
+            // KV is streamed once: a non-temporal load keeps it from displacing reusable lines
+            typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+            const u32x4 zero4 = {0u, 0u, 0u, 0u};
+            const u32x4 raw = valid ? __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p)) : zero4;
+            c.w[0] = raw[0]; c.w[1] = raw[1]; c.w[2] = raw[2]; c.w[3] = raw[3];
         } else {
             const uint2 raw = valid ? *reinterpret_cast<const uint2*>(p) : make_uint2(0, 0);
             c.w[0] = raw.x; c.w[1] = raw.y;
@@ -182,22 +185,20 @@ __global__ __launch_bounds__(kStreamThreads) void stream_attention_kernel(
     const size_t row_stride = static_cast<size_t>(n_kv_heads) * D;
     const size_t kv_base = (static_cast<size_t>(it.kv_row0) * n_kv_heads + it.kv_head) * D + sub * EPL;
 
-    Chunk<kBf16, EPL> kc[kRowsPerStep], vc[kRowsPerStep], kn[kRowsPerStep], vn[kRowsPerStep];
+    Chunk<kBf16, EPL> ka[kRowsPerStep], va[kRowsPerStep], kb[kRowsPerStep], vb[kRowsPerStep];
+    // Rows past the end are clamped to the last row (their scores are masked), so every
+    // load is unconditional and the eight loads of a step issue back to back.
     auto fetch = [&](int base, Chunk<kBf16, EPL>(&kk)[kRowsPerStep], Chunk<kBf16, EPL>(&vv)[kRowsPerStep]) {
 #pragma unroll
         for (int u = 0; u < kRowsPerStep; ++u) {
-            const int row = base + u * kStreams;
-            const bool ok = row < kv_len;
+            const int row = min(base + u * kStreams, kv_len - 1);
             const size_t off = kv_base + static_cast<size_t>(row) * row_stride;
-            kk[u] = load_chunk<kBf16, EPL>(k_, off, ok);
-            vv[u] = load_chunk<kBf16, EPL>(v_, off, ok);
+            kk[u] = load_chunk<kBf16, EPL>(k_, off, true);
+            vv[u] = load_chunk<kBf16, EPL>(v_, off, true);
         }
     };
-    if (stream < kv_len) fetch(stream, kc, vc);
-
-    for (int base = stream; base < kv_len; base += kRowsPerIter) {
-        const int next = base + kRowsPerIter;
-        if (next < kv_len) fetch(next, kn, vn);
+    // One step of the online softmax on the rows held in kc / vc (rows base + u * kStreams).
+    auto step = [&](int base, const Chunk<kBf16, EPL>(&kc)[kRowsPerStep], const Chunk<kBf16, EPL>(&vc)[kRowsPerStep]) {
 
         if constexpr (kFast) {
 #pragma unroll
@@ -249,16 +250,16 @@ __global__ __launch_bounds__(kStreamThreads) void stream_attention_kernel(
             }
         } else {
             float s[kRowsPerStep][RHO];
-    #pragma unroll
+#pragma unroll
             for (int u = 0; u < kRowsPerStep; ++u) {
-    #pragma unroll
+#pragma unroll
                 for (int e = 0; e < RHO; ++e) {
                     float part = 0.f;
                     if constexpr (kBf16) {
-    #pragma unroll
+#pragma unroll
                         for (int x = 0; x < EPL / 2; ++x) part = dot2_bf16(kc[u].w[x], qc[e].w[x], part);
                     } else {
-    #pragma unroll
+#pragma unroll
                         for (int x = 0; x < EPL; ++x) part = fmaf(qc[e].f[x], kc[u].f[x], part);
                     }
                     s[u][e] = row16_sum(part);
@@ -266,24 +267,24 @@ __global__ __launch_bounds__(kStreamThreads) void stream_attention_kernel(
             }
             // rows past the end exist only in the last iteration of a stream
             if (base + (kRowsPerStep - 1) * kStreams >= kv_len) {
-    #pragma unroll
+#pragma unroll
                 for (int u = 1; u < kRowsPerStep; ++u)
                     if (base + u * kStreams >= kv_len) {
-    #pragma unroll
+#pragma unroll
                         for (int e = 0; e < RHO; ++e) s[u][e] = -INFINITY;
                     }
             }
-    #pragma unroll
+#pragma unroll
             for (int e = 0; e < RHO; ++e) {
                 float mx = m[e];
-    #pragma unroll
+#pragma unroll
                 for (int u = 0; u < kRowsPerStep; ++u) mx = fmaxf(mx, s[u][e]);
                 // row `base` is valid, so mx is finite; m = -inf gives alpha = 0
                 const float alpha = exp2_of<kPrecise>((m[e] - mx) * c2);
                 const float mc = mx * c2;
                 float p[kRowsPerStep];
                 float psum = 0.f;
-    #pragma unroll
+#pragma unroll
                 for (int u = 0; u < kRowsPerStep; ++u) {
                     p[u] = exp2_of<kPrecise>(fmaf(s[u][e], c2, -mc));
                     psum += p[u];
@@ -296,7 +297,7 @@ __global__ __launch_bounds__(kStreamThreads) void stream_attention_kernel(
                     const bf16x2 p23v = {static_cast<__bf16>(p[2]), static_cast<__bf16>(p[3])};
                     const uint32_t p01 = __builtin_bit_cast(uint32_t, p01v);
                     const uint32_t p23 = __builtin_bit_cast(uint32_t, p23v);
-    #pragma unroll
+#pragma unroll
                     for (int x = 0; x < EPL / 2; ++x) {
                         // the same head-dim element of two rows, side by side
                         const uint32_t lo01 = __builtin_amdgcn_perm(vc[1].w[x], vc[0].w[x], 0x05040100u);
@@ -307,20 +308,40 @@ __global__ __launch_bounds__(kStreamThreads) void stream_attention_kernel(
                         acc[e][2 * x + 1] = dot2_bf16(hi23, p23, dot2_bf16(hi01, p01, acc[e][2 * x + 1] * alpha));
                     }
                 } else {
-    #pragma unroll
+#pragma unroll
                     for (int x = 0; x < EPL; ++x) {
                         float a = acc[e][x] * alpha;
-    #pragma unroll
+#pragma unroll
                         for (int u = 0; u < kRowsPerStep; ++u) a = fmaf(p[u], vc[u].f[x], a);
                         acc[e][x] = a;
                     }
                 }
             }
         }
-#pragma unroll
-        for (int u = 0; u < kRowsPerStep; ++u) {
-            kc[u] = kn[u];
-            vc[u] = vn[u];
+    };
+    // Software pipeline: the loads of step n+1 are in flight while step n computes.  The two
+    // register buffers swap roles every step (no copies), and the last step is peeled so that
+    // every prefetch inside the loop is unconditional.
+    if (stream < kv_len) {
+        int base = stream;
+        fetch(base, ka, va);
+        for (;;) {
+            if (base + kRowsPerIter >= kv_len) {
+                step(base, ka, va);
+                break;
+            }
+            fetch(base + kRowsPerIter, kb, vb);
+            __builtin_amdgcn_sched_barrier(0);
+            step(base, ka, va);
+            base += kRowsPerIter;
+            if (base + kRowsPerIter >= kv_len) {
+                step(base, kb, vb);
+                break;
+            }
+            fetch(base + kRowsPerIter, ka, va);
+            __builtin_amdgcn_sched_barrier(0);
+            step(base, kb, vb);
+            base += kRowsPerIter;
         }
     }
 
