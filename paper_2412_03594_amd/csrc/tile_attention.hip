@@ -25,8 +25,6 @@
 // its way out of LDS by the transposing 64-bit read, which also lets the lanes
 // pick the KV rows in the order the S^T accumulators hold them
 // (kv = 8i + 4h + j).  Tiles are double-buffered; one barrier per step.
-#include <cstdlib>
-
 #include "bllm_device.h"
 #include "bllm_internal.h"
 
@@ -81,9 +79,8 @@ __device__ __forceinline__ short4v lds_read_tr16(const unsigned char* lds_addr) 
 
 // NW wavefronts per workgroup, 32 stacked query rows each.  With about 200 registers a
 // wavefront, two wavefronts share a SIMD, so one runs its exp / convert work on the vector
-// ALUs while the other keeps the matrix cores busy.  BN KV rows per step; NS tile buffers in
-// LDS, so the loads of a tile are issued NS - 1 steps before it is used.
-template <int NW, int BN, int NS>
+// ALUs while the other keeps the matrix cores busy.  BN KV rows per step.
+template <int NW, int BN>
 __global__ __launch_bounds__(64 * NW, 2) void tile_attention_kernel(
     const Item* __restrict__ items, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const uint16_t* __restrict__ v, float* __restrict__ o_part, float* __restrict__ lse_part, float* __restrict__ ws_o,
@@ -92,7 +89,11 @@ __global__ __launch_bounds__(64 * NW, 2) void tile_attention_kernel(
     constexpr int kKvb = BN / 32;                    // 32-row blocks of S^T per step
     constexpr int kTileBytes = kBN * kRowBytes;
     constexpr int kBufBytes = 2 * kTileBytes;        // K tile + V tile
-    __shared__ __attribute__((aligned(1024))) unsigned char smem[NS * kBufBytes];   // [buf][K tile | V tile]
+    // Two tile buffers, each [K tile | V tile].  They are separate objects on purpose: the
+    // compiler then knows that reading one cannot touch the other, and does not make the reads
+    // of the current tile wait for the direct-to-LDS loads of the next one.
+    __shared__ __attribute__((aligned(1024))) unsigned char smem_even[kBufBytes];
+    __shared__ __attribute__((aligned(1024))) unsigned char smem_odd[kBufBytes];
 
     const Item it = items[blockIdx.x];
     const int tid = threadIdx.x;
@@ -173,10 +174,10 @@ __global__ __launch_bounds__(64 * NW, 2) void tile_attention_kernel(
         goff_k[jj] = r * row_bytes + (k_unit(lane & 15, r) << 4);
         goff_v[jj] = r * row_bytes + (v_unit(lane & 15, r) << 4);
     }
-    auto dma_tile = [&](int tile, int buf) {
+    auto dma_tile = [&](int tile, unsigned char* dst_buf) {
         const unsigned char* kt = kg + tile * tile_stride;
         const unsigned char* vt = vg + tile * tile_stride;
-        unsigned char* lds_k = smem + buf * kBufBytes + wave * kInstrPerWave * 1024;
+        unsigned char* lds_k = dst_buf + wave * kInstrPerWave * 1024;
         unsigned char* lds_v = lds_k + kTileBytes;
         const int rows_left = kv_len - tile * kBN;
         if (rows_left >= kBN) {
@@ -215,34 +216,44 @@ __global__ __launch_bounds__(64 * NW, 2) void tile_attention_kernel(
             va[db] = kTileBytes + (4 * h + e) * kRowBytes + (v_unit(4 * db + 2 * g1 + (c >> 1), e) << 4) + (c & 1) * 8;
     }
 
-    // prologue: tiles 0 .. NS-2 in flight, tile 0 landed
-#pragma unroll
-    for (int pre = 0; pre < NS - 1; ++pre)
-        if (pre < n_tiles) dma_tile(pre, pre);
-    constexpr int kDmaPerTile = 2 * kInstrPerWave;
-    if (n_tiles >= NS - 1) wait_vector_memory<(NS - 2) * kDmaPerTile>();
-    else wait_vector_memory<0>();
+    dma_tile(0, smem_even);
+    wait_vector_memory<0>();
     __syncthreads();
 
-    int buf = 0;
-    for (int tile = 0; tile < n_tiles; ++tile) {
+    // One step on the tile in `sb`, while the next tile streams into `sb_next`.
+    auto step = [&](int tile, const unsigned char* sb, unsigned char* sb_next) {
         const int tile_base = tile * kBN;
-        // the buffer of tile - 1 is free: its last readers ran before the previous barrier
-        if (tile + NS - 1 < n_tiles) dma_tile(tile + NS - 1, buf == 0 ? NS - 1 : buf - 1);
-        const unsigned char* sb = smem + buf * kBufBytes;
+        // the other buffer is free: its last readers ran before the previous barrier
+        if (tile + 1 < n_tiles) dma_tile(tile + 1, sb_next);
 
         // ---- S^T = K Q^T (64 kv x 32 queries) ---------------------------------------------------
         floatx16 sacc[kKvb];
         {
+            // K fragments are requested one group (two k-steps) ahead of the products that use
+            // them, so their LDS latency hides behind the previous group's products
+            constexpr int kGroups = 4;                 // groups of 2 k-steps
+            uint4 kf[2][2][kKvb];                      // [parity][k-step in group][kvb]
+            auto request = [&](int g, uint4 (&dst)[2][kKvb]) {
+#pragma unroll
+                for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+                    for (int kvb = 0; kvb < kKvb; ++kvb)
+                        dst[tt][kvb] = *reinterpret_cast<const uint4*>(sb + ka[2 * g + tt] + kvb * 32 * kRowBytes);
+            };
             const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            request(0, kf[0]);
 #pragma unroll
-            for (int t = 0; t < 8; ++t) {
+            for (int g = 0; g < kGroups; ++g) {
+                if (g + 1 < kGroups) request(g + 1, kf[(g + 1) & 1]);
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int kvb = 0; kvb < kKvb; ++kvb) {
-                    const uint4 raw = *reinterpret_cast<const uint4*>(sb + ka[t] + kvb * 32 * kRowBytes);
-                    sacc[kvb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, raw), qreg[t],
-                                                                         t == 0 ? zero : sacc[kvb], 0, 0, 0);
-                }
+                for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+                    for (int kvb = 0; kvb < kKvb; ++kvb)
+                        sacc[kvb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            __builtin_bit_cast(bf16x8, kf[g & 1][tt][kvb]), qreg[2 * g + tt],
+                            (g == 0 && tt == 0) ? zero : sacc[kvb], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
         if (tile_base + kBN > wave_min_vis) {       // last tile(s) of an item: mask what a row cannot see
@@ -304,13 +315,14 @@ __global__ __launch_bounds__(64 * NW, 2) void tile_attention_kernel(
                 }
             }
         }
-        // Own loads of the next tile have landed (the NS - 2 tiles after it may still be in
-        // flight; near the end of the range fewer were issued, so wait for everything); after
-        // the barrier everybody's have landed, and everybody is done reading this tile.
-        if (tile + NS - 1 < n_tiles) wait_vector_memory<(NS - 2) * kDmaPerTile>();
-        else wait_vector_memory<0>();
+        // Own loads of the next tile have landed; after the barrier everybody's have, and
+        // everybody is done reading this tile.
+        wait_vector_memory<0>();
         __syncthreads();
-        buf = buf + 1 == NS ? 0 : buf + 1;
+    };
+    for (int tile = 0; tile < n_tiles; tile += 2) {
+        step(tile, smem_even, smem_odd);
+        if (tile + 1 < n_tiles) step(tile + 1, smem_odd, smem_even);
     }
 
     // ---- epilogue: normalise and store O (transposed back), log-sum-exp --------------------------
@@ -343,21 +355,11 @@ hipError_t launch_tile_attention(const LaunchCtx& c, const Item* items, int32_t 
     const uint16_t* qq = static_cast<const uint16_t*>(q);
     const uint16_t* kk = static_cast<const uint16_t*>(k);
     const uint16_t* vv = static_cast<const uint16_t*>(v);
-#define BLLM_LAUNCH_TILE(NW_, BN_, NS_)                                                                              \
-    hipLaunchKernelGGL((tile_attention_kernel<NW_, BN_, NS_>), dim3(n_items), dim3(64 * NW_), 0, c.stream, items, qq, kk, \
-                       vv, o_part, lse_part, ws_o, ws_lse, c.desc->n_q_heads, c.desc->n_kv_heads, log2_rho, c.scale)
-    const char* ov = std::getenv("BLLM_TUNE_TILE_SHAPE");
-    const int shape = ov ? std::atoi(ov) : 0;
-    if (waves == 8) {
-        if (shape == 1) BLLM_LAUNCH_TILE(8, 64, 4);
-        else if (shape == 2) BLLM_LAUNCH_TILE(8, 64, 2);
-        else BLLM_LAUNCH_TILE(8, 64, 3);
-    } else {
-        if (shape == 1) BLLM_LAUNCH_TILE(4, 32, 4);
-        else if (shape == 2) BLLM_LAUNCH_TILE(4, 32, 5);
-        else if (shape == 3) BLLM_LAUNCH_TILE(4, 32, 3);
-        else BLLM_LAUNCH_TILE(4, 64, 2);
-    }
+#define BLLM_LAUNCH_TILE(NW_, BN_)                                                                                 \
+    hipLaunchKernelGGL((tile_attention_kernel<NW_, BN_>), dim3(n_items), dim3(64 * NW_), 0, c.stream, items, qq, kk, vv, \
+                       o_part, lse_part, ws_o, ws_lse, c.desc->n_q_heads, c.desc->n_kv_heads, log2_rho, c.scale)
+    if (waves == 8) BLLM_LAUNCH_TILE(8, 64);
+    else BLLM_LAUNCH_TILE(4, 64);
 #undef BLLM_LAUNCH_TILE
     return hipGetLastError();
 }
