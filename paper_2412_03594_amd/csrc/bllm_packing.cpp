@@ -130,7 +130,6 @@ int build_packing(const bllm_layer_desc& desc, int32_t n_groups, const int32_t* 
 
     // ---- work lists --------------------------------------------------------------------------
     const bool mfma = desc.dtype == BLLM_BF16 && desc.head_dim == 128;
-    if (const char* ov = std::getenv("BLLM_TUNE_TILE_WAVES")) p.tile_waves = std::atoi(ov) == 8 ? 8 : 4;
     p.tile_rows = mfma ? kRowsPerWave * p.tile_waves / rho : 0;
     p.prefix_row_split.assign(p.n_rows, RowSplit{0, 0, 0});
     p.suffix_row_split.assign(p.n_rows, RowSplit{0, 0, 0});

@@ -98,7 +98,7 @@ __global__ __launch_bounds__(64 * NW, 2) void tile_attention_kernel(
     const Item it = items[blockIdx.x];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wavefront-uniform, kept in a scalar register
     const int col = lane & 31;       // query column of this lane; also the A-operand row
     const int h = lane >> 5;         // lane half
     const int rho = 1 << log2_rho;
@@ -174,28 +174,36 @@ __global__ __launch_bounds__(64 * NW, 2) void tile_attention_kernel(
         goff_k[jj] = r * row_bytes + (k_unit(lane & 15, r) << 4);
         goff_v[jj] = r * row_bytes + (v_unit(lane & 15, r) << 4);
     }
-    auto dma_tile = [&](int tile, unsigned char* dst_buf) {
-        const unsigned char* kt = kg + tile * tile_stride;
-        const unsigned char* vt = vg + tile * tile_stride;
-        unsigned char* lds_k = dst_buf + wave * kInstrPerWave * 1024;
+    // One K and one V instruction (index jj) of a tile; `full` tiles use the precomputed offsets.
+    auto dma_part = [&](int tile, unsigned char* dst_buf, int jj, bool full) {
+        // tile base pointers stay in scalar registers (the empty asm keeps the loop optimiser from
+        // turning base + lane offset into one running 64-bit vector pointer per instruction)
+        uint64_t kt_bits = reinterpret_cast<uint64_t>(kg + tile * tile_stride);
+        uint64_t vt_bits = reinterpret_cast<uint64_t>(vg + tile * tile_stride);
+        asm volatile("" : "+s"(kt_bits), "+s"(vt_bits));
+        const unsigned char* kt = reinterpret_cast<const unsigned char*>(kt_bits);
+        const unsigned char* vt = reinterpret_cast<const unsigned char*>(vt_bits);
+        unsigned char* lds_k = dst_buf + (wave * kInstrPerWave + jj) * 1024;
         unsigned char* lds_v = lds_k + kTileBytes;
-        const int rows_left = kv_len - tile * kBN;
-        if (rows_left >= kBN) {
-#pragma unroll
-            for (int jj = 0; jj < kInstrPerWave; ++jj) {
-                dma16_to_lds(kt + goff_k[jj], lds_k + jj * 1024);
-                dma16_to_lds(vt + goff_v[jj], lds_v + jj * 1024);
-            }
+        if (full) {
+            // keep the lane offsets 32-bit up to the instruction (scalar base + 32-bit offset form)
+            uint32_t ok = goff_k[jj], ov = goff_v[jj];
+            asm volatile("" : "+v"(ok), "+v"(ov));
+            dma16_to_lds(kt + ok, lds_k);
+            dma16_to_lds(vt + ov, lds_v);
         } else {
             // last tile of the range: rows past the end re-read the last row (their scores are masked)
-#pragma unroll
-            for (int jj = 0; jj < kInstrPerWave; ++jj) {
-                const int r = 4 * (wave * kInstrPerWave + jj) + (lane >> 4);
-                const int rc = min(r, rows_left - 1);
-                dma16_to_lds(kt + (rc * row_bytes + (k_unit(lane & 15, r) << 4)), lds_k + jj * 1024);
-                dma16_to_lds(vt + (rc * row_bytes + (v_unit(lane & 15, r) << 4)), lds_v + jj * 1024);
-            }
+            const int rows_left = kv_len - tile * kBN;
+            const int r = 4 * (wave * kInstrPerWave + jj) + (lane >> 4);
+            const int rc = min(r, rows_left - 1);
+            dma16_to_lds(kt + (rc * row_bytes + (k_unit(lane & 15, r) << 4)), lds_k);
+            dma16_to_lds(vt + (rc * row_bytes + (v_unit(lane & 15, r) << 4)), lds_v);
         }
+    };
+    auto dma_tile = [&](int tile, unsigned char* dst_buf) {
+        const bool full = kv_len - tile * kBN >= kBN;
+#pragma unroll
+        for (int jj = 0; jj < kInstrPerWave; ++jj) dma_part(tile, dst_buf, jj, full);
     };
 
     // ---- LDS read addresses ---------------------------------------------------------------------
@@ -224,7 +232,12 @@ __global__ __launch_bounds__(64 * NW, 2) void tile_attention_kernel(
     auto step = [&](int tile, const unsigned char* sb, unsigned char* sb_next) {
         const int tile_base = tile * kBN;
         // the other buffer is free: its last readers ran before the previous barrier
-        if (tile + 1 < n_tiles) dma_tile(tile + 1, sb_next);
+        // The loads of the next tile are issued a few at a time between the groups of matrix
+        // products below, so the wavefront never sits on a full memory queue with nothing else
+        // to issue; a ragged last tile (rare) is issued up front.
+        const bool dma_next = tile + 1 < n_tiles;
+        const bool dma_spread = dma_next && kv_len - (tile + 1) * kBN >= kBN;
+        if (dma_next && !dma_spread) dma_tile(tile + 1, sb_next);
 
         // ---- S^T = K Q^T (64 kv x 32 queries) ---------------------------------------------------
         floatx16 sacc[kKvb];
@@ -245,6 +258,11 @@ __global__ __launch_bounds__(64 * NW, 2) void tile_attention_kernel(
 #pragma unroll
             for (int g = 0; g < kGroups; ++g) {
                 if (g + 1 < kGroups) request(g + 1, kf[(g + 1) & 1]);
+                if (dma_spread) {
+#pragma unroll
+                    for (int jj = g * kInstrPerWave / kGroups; jj < (g + 1) * kInstrPerWave / kGroups; ++jj)
+                        dma_part(tile + 1, sb_next, jj, true);
+                }
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int tt = 0; tt < 2; ++tt)
@@ -342,13 +360,14 @@ __global__ __launch_bounds__(64 * NW, 2) void tile_attention_kernel(
     }
 }
 
+
 }  // namespace
 
 hipError_t launch_tile_attention(const LaunchCtx& c, const Item* items, int32_t n_items, int waves, const void* q,
                                  const void* k, const void* v, float* o_part, float* lse_part, float* ws_o,
                                  float* ws_lse) {
     if (n_items <= 0) return hipSuccess;
-    if (c.desc->dtype != BLLM_BF16 || c.desc->head_dim != kD || (waves != 4 && waves != 8)) return hipErrorInvalidValue;
+    if (c.desc->dtype != BLLM_BF16 || c.desc->head_dim != kD || waves != 4) return hipErrorInvalidValue;
     const int rho = c.desc->n_q_heads / c.desc->n_kv_heads;
     int log2_rho = 0;
     while ((1 << log2_rho) < rho) ++log2_rho;
@@ -358,8 +377,7 @@ hipError_t launch_tile_attention(const LaunchCtx& c, const Item* items, int32_t 
 #define BLLM_LAUNCH_TILE(NW_, BN_)                                                                                 \
     hipLaunchKernelGGL((tile_attention_kernel<NW_, BN_>), dim3(n_items), dim3(64 * NW_), 0, c.stream, items, qq, kk, vv, \
                        o_part, lse_part, ws_o, ws_lse, c.desc->n_q_heads, c.desc->n_kv_heads, log2_rho, c.scale)
-    if (waves == 8) BLLM_LAUNCH_TILE(8, 64);
-    else BLLM_LAUNCH_TILE(4, 64);
+    BLLM_LAUNCH_TILE(4, 64);
 #undef BLLM_LAUNCH_TILE
     return hipGetLastError();
 }
