@@ -89,8 +89,8 @@ def pack_token_batch(prefix_len, req_group, req_suffix_len, req_q_len):
 ITEM_INTS = 8
 
 SPLIT_WHEN_BELOW = 512      # split prefixes when fewer tile items than this would exist
-SPLIT_TARGET_ITEMS = 1024
-MIN_SPLIT_LEN = 256
+SPLIT_TARGET_ITEMS = 512
+MIN_SPLIT_LEN = 512
 KV_TILE = 64
 
 
@@ -176,6 +176,8 @@ def build_work_lists(meta, prefix_len, req_suffix_len, req_q_len, n_q_heads, n_k
         for t in range(T):
             for j in range(n_kv_heads):
                 suffix_rows.append([t, 1, j, rks[row_req[t]], row_pos[t] + 1, row_pos[t] + 1, -1, 0])
+    # prefix tile items: longest KV range first (stable); suffix tile items keep request order
+    prefix_tiles.sort(key=lambda it: -it[4])
     # streaming items: longest range first (stable)
     key = lambda it: -min(it[4], it[5])
     prefix_rows.sort(key=key)

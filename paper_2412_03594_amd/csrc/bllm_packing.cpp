@@ -16,8 +16,8 @@ namespace {
 constexpr int kRowsPerWave = 32;         // stacked query rows (token rows x heads per KV head) per wavefront
 constexpr int kKvTile = 64;             // KV rows per MFMA inner step; split lengths are multiples of it
 constexpr int kSplitWhenBelow = 512;    // split the prefix when fewer tile items than this exist
-constexpr int kSplitTargetItems = 1024;
-constexpr int kMinSplitLen = 256;
+constexpr int kSplitTargetItems = 512;  // two workgroups per compute unit
+constexpr int kMinSplitLen = 512;       // shorter splits cost more in partial-result traffic than they gain
 
 bool fits_i32(int64_t v) { return v >= 0 && v <= std::numeric_limits<int32_t>::max(); }
 
@@ -234,6 +234,12 @@ int build_packing(const bllm_layer_desc& desc, int32_t n_groups, const int32_t* 
         *wpi = mean >= 192 ? 4 : mean >= 96 ? 2 : 1;
         if (const char* ov = std::getenv("BLLM_TUNE_STREAM_WPI")) *wpi = std::atoi(ov) == 1 ? 1 : std::atoi(ov) == 2 ? 2 : 4;
     };
+    // Prefix tile items: longest KV range first as well (stable: the items of a group stay together
+    // and keep sharing its K/V in L2, the KV heads of one row block stay adjacent).  The chunk
+    // items of the suffix pass keep their request order, which measured faster (K/V reuse between
+    // the row blocks of one request).
+    std::stable_sort(p.prefix_tile_items.begin(), p.prefix_tile_items.end(),
+                     [](const Item& a, const Item& b) { return a.kv_len > b.kv_len; });
     finish_stream_list(p.prefix_row_items, &p.prefix_stream_wpi);
     finish_stream_list(p.suffix_row_items, &p.suffix_stream_wpi);
     return BLLM_OK;
