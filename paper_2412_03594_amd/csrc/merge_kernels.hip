@@ -8,10 +8,20 @@
 #include "bllm_device.h"
 #include "bllm_internal.h"
 
+#include <type_traits>
+
 namespace bllm {
 namespace {
 
 constexpr int kMergeThreads = 256;
+
+typedef float float4v __attribute__((ext_vector_type(4)));
+
+// 16-byte load of data that is read exactly once (does not displace what the caches hold)
+__device__ __forceinline__ float4 load_once(const float* p) {
+    const float4v r = __builtin_nontemporal_load(reinterpret_cast<const float4v*>(p));
+    return make_float4(r[0], r[1], r[2], r[3]);
+}
 
 template <bool kBf16Out>
 __global__ __launch_bounds__(kMergeThreads) void lse_merge_kernel(
@@ -22,6 +32,11 @@ __global__ __launch_bounds__(kMergeThreads) void lse_merge_kernel(
     const int64_t rh = gid / quads_per_row_head;
     if (rh >= n_row_heads) return;
     const int quad = static_cast<int>(gid - rh * quads_per_row_head);
+    const size_t off = static_cast<size_t>(rh) * quads_per_row_head * 4 + quad * 4;
+    // An empty part's rows are specified as 0, but never multiply garbage by 0.  The loads do not
+    // wait for the weights: both rows are fetched at once and an empty part's values are dropped.
+    const float4 ra = load_once(o_a + off);
+    const float4 rb = load_once(o_b + off);
     const float la = lse_a[rh];
     const float lb = lse_b[rh];
     const float top = fmaxf(la, lb);
@@ -37,10 +52,8 @@ __global__ __launch_bounds__(kMergeThreads) void lse_merge_kernel(
         inv = 1.f / tot;
         lse = top + logf(tot);
     }
-    const size_t off = static_cast<size_t>(rh) * quads_per_row_head * 4 + quad * 4;
-    // An empty part's rows are specified as 0, but never multiply garbage by 0.
-    const float4 a = wa > 0.f ? *reinterpret_cast<const float4*>(o_a + off) : make_float4(0.f, 0.f, 0.f, 0.f);
-    const float4 b = wb > 0.f ? *reinterpret_cast<const float4*>(o_b + off) : make_float4(0.f, 0.f, 0.f, 0.f);
+    const float4 a = wa > 0.f ? ra : make_float4(0.f, 0.f, 0.f, 0.f);
+    const float4 b = wb > 0.f ? rb : make_float4(0.f, 0.f, 0.f, 0.f);
     float4 r;
     r.x = (wa * a.x + wb * b.x) * inv;
     r.y = (wa * a.y + wb * b.y) * inv;
@@ -67,20 +80,51 @@ __global__ __launch_bounds__(kMergeThreads) void split_combine_kernel(
     const int head = static_cast<int>(rh - row * n_q_heads);
     const RowSplit sp = row_split[row];
     if (sp.n_splits <= 0) return;      // this row was written directly by the pass
+    // Splits are taken four at a time (two for a row with two splits): their log-sum-exps and
+    // rows are fetched together, then folded into the running (maximum, numerator, denominator).
+    const size_t rh_stride = static_cast<size_t>(sp.stride) * n_q_heads;             // between splits
+    const size_t wrh0 = static_cast<size_t>(sp.ws_row0) * n_q_heads + head;
+    const size_t elem = static_cast<size_t>(quads_per_row_head) * 4;
     float top = -INFINITY;
-    for (int c = 0; c < sp.n_splits; ++c)
-        top = fmaxf(top, ws_lse[(static_cast<size_t>(sp.ws_row0) + static_cast<size_t>(c) * sp.stride) * n_q_heads + head]);
     float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
     float den = 0.f;
-    for (int c = 0; c < sp.n_splits; ++c) {
-        const size_t wrh = (static_cast<size_t>(sp.ws_row0) + static_cast<size_t>(c) * sp.stride) * n_q_heads + head;
-        const float w = expf(ws_lse[wrh] - top);
-        const float4 x = *reinterpret_cast<const float4*>(ws_o + wrh * quads_per_row_head * 4 + quad * 4);
-        num.x = fmaf(w, x.x, num.x);
-        num.y = fmaf(w, x.y, num.y);
-        num.z = fmaf(w, x.z, num.z);
-        num.w = fmaf(w, x.w, num.w);
-        den += w;
+    auto fold = [&](auto width, int c0) {
+        constexpr int kW = decltype(width)::value;
+        float l[kW];
+        float4 x[kW];
+#pragma unroll
+        for (int i = 0; i < kW; ++i) {
+            const int c = min(c0 + i, sp.n_splits - 1);      // past the end: re-read the last split (unused)
+            const size_t wrh = wrh0 + c * rh_stride;
+            l[i] = ws_lse[wrh];
+            x[i] = load_once(ws_o + wrh * elem + quad * 4);
+        }
+        float m = top;
+#pragma unroll
+        for (int i = 0; i < kW; ++i)
+            if (c0 + i < sp.n_splits) m = fmaxf(m, l[i]);
+        const float r = top == -INFINITY ? 0.f : expf(top - m);
+        num.x *= r;
+        num.y *= r;
+        num.z *= r;
+        num.w *= r;
+        den *= r;
+        top = m;
+#pragma unroll
+        for (int i = 0; i < kW; ++i)
+            if (c0 + i < sp.n_splits) {
+                const float w = expf(l[i] - m);
+                num.x = fmaf(w, x[i].x, num.x);
+                num.y = fmaf(w, x[i].y, num.y);
+                num.z = fmaf(w, x[i].z, num.z);
+                num.w = fmaf(w, x[i].w, num.w);
+                den += w;
+            }
+    };
+    if (sp.n_splits <= 2) {
+        fold(std::integral_constant<int, 2>{}, 0);
+    } else {
+        for (int c0 = 0; c0 < sp.n_splits; c0 += 4) fold(std::integral_constant<int, 4>{}, c0);
     }
     const float inv = 1.f / den;       // every split of a split row holds at least one key
     const size_t off = static_cast<size_t>(rh) * quads_per_row_head * 4 + quad * 4;
