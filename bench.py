@@ -53,7 +53,10 @@ def algorithmic_work(batch, meta):
     suffix = {"bytes": float(2 * (s * act).sum() * hkv * d * e + q_bytes + part_bytes),
               "flops": float(4 * hq * d * vis_sum.sum())}
     merge = {"bytes": float(T * hq * (2 * (4 * d + 4) + e * d)), "flops": 0.0}
-    return {"prefix": prefix, "suffix": suffix, "merge": merge}
+    # suffix pass with the reduction in its epilogue: reads the prefix partial instead of writing its
+    # own, and writes the final output
+    suffix_merged = {"bytes": suffix["bytes"] + float(T * hq * d * e), "flops": suffix["flops"]}
+    return {"prefix": prefix, "suffix": suffix, "merge": merge, "suffix_merged": suffix_merged}
 
 
 def time_loop(fn, steps, warmup, torch):
@@ -107,7 +110,8 @@ def oracle_baseline(batch, vals, budget_s=15.0):
                       (done_reqs, len(order), len(by_group), done_rows, dt)}
 
 
-def run_workload(name, steps, warmup, seed, rotate, torch, bllm, workload, with_values_host=True):
+def run_workload(name, steps, warmup, seed, rotate, torch, bllm, workload, with_values_host=True, schedule="fused",
+                 use_graph=False):
     batch = workload.CONFIGS[name](seed)
     L = batch.layer
     dev = torch.device("cuda:0")
@@ -128,7 +132,13 @@ def run_workload(name, steps, warmup, seed, rotate, torch, bllm, workload, with_
         q = mk(T, L.n_q_heads)
         kv = [[mk(batch.n_prefix_kv, L.n_kv_heads), mk(batch.n_prefix_kv, L.n_kv_heads),
                mk(batch.n_suffix_kv, L.n_kv_heads), mk(batch.n_suffix_kv, L.n_kv_heads)]]
-    # Rotating copies of the KV keep a step from being served out of the 256 MB Infinity Cache.
+    # Rotating copies of the KV keep a step - and each pass timed alone - from being served out of
+    # the 256 MB Infinity Cache: enough copies that the smaller of the two KV sets cycles through
+    # more than 512 MB (rotate = 0), or the number asked for.
+    if rotate <= 0:
+        e = 2 if L.dtype == workload.BF16 else 4
+        kv_set = 2 * L.n_kv_heads * L.head_dim * e * max(1, min(batch.n_prefix_kv, batch.n_suffix_kv))
+        rotate = int(min(16, max(2, -(-(512 << 20) // kv_set))))
     for _ in range(rotate - 1):
         kv.append([t.clone() for t in kv[0]])
     o1 = torch.empty((T, L.n_q_heads, L.head_dim), device=dev, dtype=torch.float32)
@@ -153,35 +163,73 @@ def run_workload(name, steps, warmup, seed, rotate, torch, bllm, workload, with_
     def merge_pass():
         bllm.lse_merge(pg, o1, l1, o2, l2, o, None)
 
-    def step():
+    def suffix_merged_pass():
+        b = nxt()
+        bllm.suffix_attention_merged(pg, q, b[2], b[3], o1, l1, o, None)
+
+    def step_three_call():
         b = nxt()
         bllm.shared_prefix_attention(pg, q, b[0], b[1], o1, l1)
         bllm.suffix_attention(pg, q, b[2], b[3], o2, l2)
         bllm.lse_merge(pg, o1, l1, o2, l2, o, None)
 
+    def step_fused():
+        b = nxt()
+        bllm.shared_prefix_attention(pg, q, b[0], b[1], o1, l1)
+        bllm.suffix_attention_merged(pg, q, b[2], b[3], o1, l1, o, None)
+
+    step = step_fused if schedule == "fused" else step_three_call
+
+    # One captured HIP graph per KV copy: a replay is exactly one step; the launches of a step reach
+    # the GPU as one submission, without per-kernel launch gaps.
+    graphs = []
+    if use_graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for _ in range(2 * len(kv)):
+                step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        for _ in range(len(kv)):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                step()
+            graphs.append(g)
+        state["g"] = 0
+
+        def step_graph():
+            state["g"] = (state["g"] + 1) % len(graphs)
+            graphs[state["g"]].replay()
+        timed_step = step_graph
+    else:
+        timed_step = step
+
     # whole-step timing: K steps bracketed by synchronisation on both sides
     for _ in range(warmup):
-        step()
+        timed_step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(steps):
-        step()
+        timed_step()
     torch.cuda.synchronize()
     ms_step = (time.perf_counter() - t0) * 1e3 / steps
 
     # per-pass launch durations with events on the launch stream
     t_pass = {"prefix": time_loop(prefix_pass, steps, warmup, torch),
               "suffix": time_loop(suffix_pass, steps, warmup, torch),
-              "merge": time_loop(merge_pass, steps, warmup, torch)}
+              "merge": time_loop(merge_pass, steps, warmup, torch),
+              "suffix_merged": time_loop(suffix_merged_pass, steps, warmup, torch)}
     work = algorithmic_work(batch, meta)
     passes = {}
-    for k in ("prefix", "suffix", "merge"):
+    for k in ("prefix", "suffix", "merge", "suffix_merged"):
         sec = t_pass[k] * 1e-3
         passes[k] = {"ms": round(t_pass[k], 5), "GB_s": round(work[k]["bytes"] / sec / 1e9, 1),
                      "TFLOP_s": round(work[k]["flops"] / sec / 1e12, 2),
                      "alg_MB": round(work[k]["bytes"] / 1e6, 2), "alg_GFLOP": round(work[k]["flops"] / 1e9, 2)}
     res = {"batch": batch, "vals": vals, "meta": meta, "ms_step": ms_step, "passes": passes, "work": work,
-           "t_pass": t_pass, "tokens": T}
+           "t_pass": t_pass, "tokens": T, "schedule": schedule, "rotate": rotate, "graph": bool(graphs)}
+    graphs.clear()
     pg.destroy()
     return res
 
@@ -189,7 +237,8 @@ def run_workload(name, steps, warmup, seed, rotate, torch, bllm, workload, with_
 def roofline_of(res):
     """Roofline record of the pass that takes the most time."""
     t = res["t_pass"]
-    name = max(("prefix", "suffix", "merge"), key=lambda k: t[k])
+    in_step = ("prefix", "suffix_merged") if res["schedule"] == "fused" else ("prefix", "suffix", "merge")
+    name = max(in_step, key=lambda k: t[k])
     traffic = MEASURED_TRAFFIC_BYTES.get(res["batch"].name, {}).get(name)
     w = res["work"][name]
     sec = t[name] * 1e-3
@@ -201,7 +250,8 @@ def roofline_of(res):
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(a / PEAK_BF16_TFLOPS, 4), "traffic": traffic}
     a = w["bytes"] / sec / 1e9
     kern = {"prefix": "tile_attention_kernel (shared-prefix pass)",
-            "suffix": "stream_attention_kernel (distinct-suffix pass)", "merge": "lse_merge_kernel"}[name]
+            "suffix": "stream_attention_kernel (distinct-suffix pass)", "merge": "lse_merge_kernel",
+            "suffix_merged": "stream_attention_kernel (distinct-suffix pass, reduction in the epilogue)"}[name]
     return {"kernel": kern, "bound": "hbm", "achieved": round(a, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
             "frac": round(a / PEAK_HBM_GBS, 4), "traffic": traffic}
 
@@ -215,7 +265,14 @@ def main():
     ap.add_argument("--also", default="rank_longprefix,l8b_mixed",
                     help="comma-separated extra workloads reported under 'other_workloads' ('' for none)")
     ap.add_argument("--seed", type=int, default=0)
-    ap.add_argument("--rotate", type=int, default=2, help="copies of the KV tensors cycled through")
+    ap.add_argument("--rotate", type=int, default=0,
+                    help="copies of the KV tensors cycled through (0: enough to defeat the Infinity Cache, 2..16)")
+    ap.add_argument("--schedule", choices=["fused", "three_call"], default="fused",
+                    help="timed step: prefix pass + suffix pass with the reduction in its epilogue (two calls), "
+                         "or prefix, suffix and merge passes (three calls); both give the same final output")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay one captured HIP graph per timed step instead of launching eagerly (measured slower "
+                         "than eager launches on the decode workload, faster on the long-running ones)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device-to-device copy (reference for HBM byte counters)")
@@ -239,7 +296,8 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
 
-    main_res = run_workload(args.workload, args.steps, args.warmup, args.seed, args.rotate, torch, bllm, workload)
+    main_res = run_workload(args.workload, args.steps, args.warmup, args.seed, args.rotate, torch, bllm, workload,
+                            schedule=args.schedule, use_graph=args.graph)
     batch = main_res["batch"]
     L = batch.layer
     out = {
@@ -255,7 +313,8 @@ def main():
                    "n_kv_heads": L.n_kv_heads, "head_dim": L.head_dim, "groups": batch.n_groups,
                    "requests": batch.n_requests, "token_rows": batch.n_rows,
                    "prefix_kv_rows": batch.n_prefix_kv, "suffix_kv_rows": batch.n_suffix_kv,
-                   "kv_copies_rotated": args.rotate},
+                   "kv_copies_rotated": main_res["rotate"], "schedule": args.schedule,
+                   "launch": "hip graph replay, one graph per step" if main_res["graph"] else "eager"},
         "roofline": roofline_of(main_res),
         "passes": main_res["passes"],
     }
@@ -264,7 +323,7 @@ def main():
     others = {}
     for name in [n for n in args.also.split(",") if n and n != args.workload]:
         r = run_workload(name, max(20, args.steps // 4), max(5, args.warmup // 2), args.seed, args.rotate, torch,
-                         bllm, workload)
+                         bllm, workload, schedule=args.schedule, use_graph=args.graph)
         others[name] = {"tokens_per_s": round(r["tokens"] / (r["ms_step"] * 1e-3), 1),
                         "ms_per_step": round(r["ms_step"], 5), "token_rows": r["tokens"],
                         "roofline": roofline_of(r), "passes": r["passes"]}

@@ -171,6 +171,26 @@ int bllm_lse_merge(const bllm_prefix_groups* pg,
                    const float* o_b, const float* lse_b,
                    void* o_out, float* lse_out, void* hip_stream);
 
+/* Distinct-suffix pass with the reduction fused into its epilogue (Sec. 4.3.3:
+ * the partial attention on the distinct part, Sec. 5: reduced with the result of
+ * the shared-context part through online softmax - here without a separate
+ * reduction kernel and without storing the suffix partial).  The result equals
+ * bllm_suffix_attention followed by bllm_lse_merge(o_prefix, lse_prefix,
+ * suffix partial) up to fp32 rounding.
+ *   q, k_suffix, v_suffix    as for bllm_suffix_attention
+ *   o_prefix   device [T,Hq,D] fp32, lse_prefix device [T,Hq] fp32: the output of
+ *              bllm_shared_prefix_attention for the same handle and q; read only,
+ *              must be complete on hip_stream before this call runs (same stream,
+ *              or ordered by the caller)
+ *   o_out      device [T,Hq,D] desc.dtype   final attention output, every element written
+ *   lse_out    device [T,Hq] fp32 final log-sum-exp, or NULL
+ * Returns BLLM_UNSUPPORTED if the handle splits suffix KV ranges (it never does at
+ * present); otherwise errors as the other device calls.  Allocates nothing. */
+int bllm_suffix_attention_merged(const bllm_prefix_groups* pg, const void* q,
+                                 const void* k_suffix, const void* v_suffix,
+                                 const float* o_prefix, const float* lse_prefix,
+                                 void* o_out, float* lse_out, void* hip_stream);
+
 const char* bllm_last_error(void);
 const char* bllm_version(void);
 

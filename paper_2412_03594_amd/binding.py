@@ -14,7 +14,7 @@ _LIB = None
 
 EXPORTS = ["bllm_prefix_group_create", "bllm_prefix_group_create_host", "bllm_prefix_group_metadata",
            "bllm_prefix_group_destroy", "bllm_shared_prefix_attention", "bllm_suffix_attention", "bllm_lse_merge",
-           "bllm_last_error", "bllm_version"]
+           "bllm_suffix_attention_merged", "bllm_last_error", "bllm_version"]
 
 
 class BllmError(RuntimeError):
@@ -70,7 +70,9 @@ def load_library():
         getattr(lib, name).argtypes = [h, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.bllm_lse_merge.argtypes = [h, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                    C.c_void_p]
-    for name in EXPORTS[:7]:
+    lib.bllm_suffix_attention_merged.argtypes = [h, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                                 C.c_void_p, C.c_void_p, C.c_void_p]
+    for name in EXPORTS[:8]:
         getattr(lib, name).restype = C.c_int
     lib.bllm_last_error.restype = C.c_char_p
     lib.bllm_version.restype = C.c_char_p
@@ -192,14 +194,24 @@ def suffix_attention(pg, q, k_suffix, v_suffix, o_part, lse_part, stream=None):
                                                 _ptr(lse_part), _stream(stream)))
 
 
+def suffix_attention_merged(pg, q, k_suffix, v_suffix, o_prefix, lse_prefix, o_out, lse_out=None, stream=None):
+    _check(load_library().bllm_suffix_attention_merged(pg.handle, _ptr(q), _ptr(k_suffix), _ptr(v_suffix), _ptr(o_prefix),
+                                                       _ptr(lse_prefix), _ptr(o_out), _ptr(lse_out), _stream(stream)))
+
+
 def lse_merge(pg, o_a, lse_a, o_b, lse_b, o_out, lse_out=None, stream=None):
     _check(load_library().bllm_lse_merge(pg.handle, _ptr(o_a), _ptr(lse_a), _ptr(o_b), _ptr(lse_b), _ptr(o_out),
                                          _ptr(lse_out), _stream(stream)))
 
 
-def prefix_shared_attention(pg, q, k_prefix, v_prefix, k_suffix, v_suffix, bufs, stream=None):
-    """The three device calls in sequence on one stream.  bufs: dict with preallocated
-    o1, l1, o2, l2 (fp32 partials), o (layer dtype) and optionally lse."""
+def prefix_shared_attention(pg, q, k_prefix, v_prefix, k_suffix, v_suffix, bufs, stream=None, fused=False):
+    """The device calls of the path in sequence on one stream.  bufs: dict with preallocated
+    o1, l1 (fp32 partials of the prefix pass), o (layer dtype), optionally lse, and - for the
+    three-call sequence - o2, l2 (fp32 partials of the suffix pass).  fused=True uses the suffix
+    pass that merges in its epilogue (two calls, no o2 / l2)."""
     shared_prefix_attention(pg, q, k_prefix, v_prefix, bufs["o1"], bufs["l1"], stream)
+    if fused:
+        suffix_attention_merged(pg, q, k_suffix, v_suffix, bufs["o1"], bufs["l1"], bufs["o"], bufs.get("lse"), stream)
+        return
     suffix_attention(pg, q, k_suffix, v_suffix, bufs["o2"], bufs["l2"], stream)
     lse_merge(pg, bufs["o1"], bufs["l1"], bufs["o2"], bufs["l2"], bufs["o"], bufs.get("lse"), stream)

@@ -239,11 +239,18 @@ int bllm_prefix_group_destroy(bllm_prefix_groups* pg) {
     return rc;
 }
 
+// One attention pass.  With a merge target the pass writes the merged final output instead of
+// its own partial (o_part / lse_part are then unused).
 static int run_pass(const bllm_prefix_groups* pg, bool prefix, const void* q, const void* k, const void* v,
-                    float* o_part, float* lse_part, void* hip_stream) {
-    int rc = check_device_call(pg, {q, o_part, lse_part});
+                    float* o_part, float* lse_part, const MergeTarget& mt, void* hip_stream) {
+    const bool fused = mt.o_a != nullptr;
+    int rc = fused ? check_device_call(pg, {q, mt.o_a, mt.lse_a, mt.o_out}) : check_device_call(pg, {q, o_part, lse_part});
     if (rc != BLLM_OK) return rc;
     const Packing& p = pg->pk;
+    if (fused && (prefix ? p.prefix_has_split : p.suffix_has_split)) {
+        set_error("a pass whose KV ranges are split cannot merge in its epilogue");
+        return BLLM_UNSUPPORTED;
+    }
     if (p.n_rows == 0) return BLLM_OK;
     const auto& tiles = prefix ? p.prefix_tile_items : p.suffix_tile_items;
     const auto& rows = prefix ? p.prefix_row_items : p.suffix_row_items;
@@ -257,13 +264,13 @@ static int run_pass(const bllm_prefix_groups* pg, bool prefix, const void* q, co
     if (!tiles.empty()) {
         e = launch_tile_attention(c, prefix ? pg->d.prefix_tile_items : pg->d.suffix_tile_items,
                                   static_cast<int32_t>(tiles.size()), p.tile_waves, q, k, v, o_part, lse_part, pg->d.ws_o,
-                                  pg->d.ws_lse);
+                                  pg->d.ws_lse, mt);
         if (e != hipSuccess) return hip_fail(e, "tile attention launch");
     }
     if (!rows.empty()) {
         e = launch_stream_attention(c, prefix ? pg->d.prefix_row_items : pg->d.suffix_row_items,
                                     static_cast<int32_t>(rows.size()), prefix ? p.prefix_stream_wpi : p.suffix_stream_wpi, q, k, v,
-                                    o_part, lse_part, pg->d.ws_o, pg->d.ws_lse);
+                                    o_part, lse_part, pg->d.ws_o, pg->d.ws_lse, mt);
         if (e != hipSuccess) return hip_fail(e, "streaming attention launch");
     }
     if (prefix ? p.prefix_has_split : p.suffix_has_split) {
@@ -276,12 +283,27 @@ static int run_pass(const bllm_prefix_groups* pg, bool prefix, const void* q, co
 
 int bllm_shared_prefix_attention(const bllm_prefix_groups* pg, const void* q, const void* k_prefix,
                                  const void* v_prefix, float* o_part, float* lse_part, void* hip_stream) {
-    return run_pass(pg, true, q, k_prefix, v_prefix, o_part, lse_part, hip_stream);
+    return run_pass(pg, true, q, k_prefix, v_prefix, o_part, lse_part, MergeTarget{}, hip_stream);
 }
 
 int bllm_suffix_attention(const bllm_prefix_groups* pg, const void* q, const void* k_suffix, const void* v_suffix,
                           float* o_part, float* lse_part, void* hip_stream) {
-    return run_pass(pg, false, q, k_suffix, v_suffix, o_part, lse_part, hip_stream);
+    return run_pass(pg, false, q, k_suffix, v_suffix, o_part, lse_part, MergeTarget{}, hip_stream);
+}
+
+int bllm_suffix_attention_merged(const bllm_prefix_groups* pg, const void* q, const void* k_suffix, const void* v_suffix,
+                                 const float* o_prefix, const float* lse_prefix, void* o_out, float* lse_out,
+                                 void* hip_stream) {
+    if (pg && pg->on_device && pg->pk.n_rows > 0 && (!o_prefix || !lse_prefix || !o_out)) {
+        set_error("null tensor pointer");
+        return BLLM_INVALID_ARG;
+    }
+    MergeTarget mt;
+    mt.o_a = o_prefix;
+    mt.lse_a = lse_prefix;
+    mt.o_out = o_out;
+    mt.lse_out = lse_out;
+    return run_pass(pg, false, q, k_suffix, v_suffix, nullptr, nullptr, mt, hip_stream);
 }
 
 int bllm_lse_merge(const bllm_prefix_groups* pg, const float* o_a, const float* lse_a, const float* o_b,

@@ -27,6 +27,42 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
     return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
 }
 
+// Online-softmax merge of two normalised partial results (BatchLLM Sec. 5) with natural-log
+// log-sum-exps la, lb: out = (wa * a + wb * b) * inv, lse as returned.  An empty part (-inf) gets
+// weight exactly 0; two empty parts give weights 0, inv 0 and lse -inf.
+struct MergeWeights {
+    float wa, wb, inv, lse;
+};
+__device__ __forceinline__ MergeWeights merge_weights(float la, float lb) {
+    MergeWeights w;
+    const float top = fmaxf(la, lb);
+    if (top == -INFINITY) {
+        w.wa = w.wb = 0.f;
+        w.inv = 0.f;
+        w.lse = -INFINITY;
+    } else {
+        w.wa = expf(la - top);         // exp(-inf) = 0 for an empty part
+        w.wb = expf(lb - top);
+        const float tot = w.wa + w.wb;
+        w.inv = 1.f / tot;
+        w.lse = top + logf(tot);
+    }
+    return w;
+}
+// one merged element; a value of a part with weight 0 is dropped, never multiplied
+__device__ __forceinline__ float merge_value(const MergeWeights& w, float a, float b) {
+    return (w.wa * (w.wa > 0.f ? a : 0.f) + w.wb * (w.wb > 0.f ? b : 0.f)) * w.inv;
+}
+// Stores 4 consecutive merged elements at element offset `off` of an output in the layer's dtype.
+template <bool kBf16Out>
+__device__ __forceinline__ void store_out4(void* out, size_t off, float x0, float x1, float x2, float x3) {
+    if constexpr (kBf16Out) {
+        *reinterpret_cast<uint2*>(static_cast<uint16_t*>(out) + off) = make_uint2(pack_bf16(x0, x1), pack_bf16(x2, x3));
+    } else {
+        *reinterpret_cast<float4*>(static_cast<float*>(out) + off) = make_float4(x0, x1, x2, x3);
+    }
+}
+
 // Data-parallel-primitive lane exchange inside a row of 16 lanes.
 template <int kCtrl>
 __device__ __forceinline__ float dpp_move(float x) {

@@ -86,12 +86,22 @@ struct LaunchCtx {
     hipStream_t stream;
 };
 
+// Fused merge: when o_a is not null, an attention kernel merges its own result with the other
+// part (o_a, lse_a) in its epilogue and writes the final output (layer dtype) to o_out, and the
+// final log-sum-exp to lse_out when that is not null, instead of writing its fp32 partial.
+struct MergeTarget {
+    const float* o_a = nullptr;    // [n_rows, Hq, D]
+    const float* lse_a = nullptr;  // [n_rows, Hq]
+    void* o_out = nullptr;         // [n_rows, Hq, D] in the layer's dtype
+    float* lse_out = nullptr;      // [n_rows, Hq] or null
+};
+
 hipError_t launch_stream_attention(const LaunchCtx& c, const Item* items, int32_t n_items, int waves_per_item,
                                    const void* q, const void* k, const void* v, float* o_part, float* lse_part,
-                                   float* ws_o, float* ws_lse);
+                                   float* ws_o, float* ws_lse, const MergeTarget& mt);
 hipError_t launch_tile_attention(const LaunchCtx& c, const Item* items, int32_t n_items, int waves, const void* q,
                                  const void* k, const void* v, float* o_part, float* lse_part, float* ws_o,
-                                 float* ws_lse);
+                                 float* ws_lse, const MergeTarget& mt);
 hipError_t launch_split_combine(const LaunchCtx& c, const RowSplit* row_split, const float* ws_o, const float* ws_lse,
                                 float* o_part, float* lse_part);
 hipError_t launch_lse_merge(const LaunchCtx& c, const float* o_a, const float* lse_a, const float* o_b,

@@ -37,35 +37,10 @@ __global__ __launch_bounds__(kMergeThreads) void lse_merge_kernel(
     // wait for the weights: both rows are fetched at once and an empty part's values are dropped.
     const float4 ra = load_once(o_a + off);
     const float4 rb = load_once(o_b + off);
-    const float la = lse_a[rh];
-    const float lb = lse_b[rh];
-    const float top = fmaxf(la, lb);
-    float wa, wb, inv, lse;
-    if (top == -INFINITY) {            // both parts empty
-        wa = wb = 0.f;
-        inv = 0.f;
-        lse = -INFINITY;
-    } else {
-        wa = expf(la - top);           // exp(-inf) = 0 for an empty part
-        wb = expf(lb - top);
-        const float tot = wa + wb;
-        inv = 1.f / tot;
-        lse = top + logf(tot);
-    }
-    const float4 a = wa > 0.f ? ra : make_float4(0.f, 0.f, 0.f, 0.f);
-    const float4 b = wb > 0.f ? rb : make_float4(0.f, 0.f, 0.f, 0.f);
-    float4 r;
-    r.x = (wa * a.x + wb * b.x) * inv;
-    r.y = (wa * a.y + wb * b.y) * inv;
-    r.z = (wa * a.z + wb * b.z) * inv;
-    r.w = (wa * a.w + wb * b.w) * inv;
-    if constexpr (kBf16Out) {
-        uint2 packed = make_uint2(pack_bf16(r.x, r.y), pack_bf16(r.z, r.w));
-        *reinterpret_cast<uint2*>(static_cast<uint16_t*>(o_out) + off) = packed;
-    } else {
-        *reinterpret_cast<float4*>(static_cast<float*>(o_out) + off) = r;
-    }
-    if (lse_out != nullptr && quad == 0) lse_out[rh] = lse;
+    const MergeWeights w = merge_weights(lse_a[rh], lse_b[rh]);
+    store_out4<kBf16Out>(o_out, off, merge_value(w, ra.x, rb.x), merge_value(w, ra.y, rb.y), merge_value(w, ra.z, rb.z),
+                         merge_value(w, ra.w, rb.w));
+    if (lse_out != nullptr && quad == 0) lse_out[rh] = w.lse;
 }
 
 __global__ __launch_bounds__(kMergeThreads) void split_combine_kernel(

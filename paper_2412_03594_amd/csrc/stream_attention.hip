@@ -120,7 +120,7 @@ template <bool kBf16, int D, int RHO, int WPI>
 __global__ __launch_bounds__(kStreamThreads) void stream_attention_kernel(
     const Item* __restrict__ items, int n_items, const void* __restrict__ q_, const void* __restrict__ k_,
     const void* __restrict__ v_, float* __restrict__ o_part, float* __restrict__ lse_part, float* __restrict__ ws_o,
-    float* __restrict__ ws_lse, int n_q_heads, int n_kv_heads, float scale) {
+    float* __restrict__ ws_lse, int n_q_heads, int n_kv_heads, float scale, MergeTarget mt) {
     constexpr int EPL = D / 16;
     constexpr bool kPrecise = !kBf16;
     constexpr int kItemsPerBlock = kWavesPerBlock / WPI;
@@ -128,7 +128,7 @@ __global__ __launch_bounds__(kStreamThreads) void stream_attention_kernel(
     constexpr int kRowsPerIter = kStreams * kRowsPerStep;
     __shared__ float sm_m[kItemsPerBlock][WPI][RHO];
     __shared__ float sm_l[kItemsPerBlock][WPI][RHO];
-    __shared__ float sm_acc[kItemsPerBlock][WPI][RHO][D];
+    __shared__ __attribute__((aligned(16))) float sm_acc[kItemsPerBlock][WPI][RHO][D];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -159,6 +159,40 @@ __global__ __launch_bounds__(kStreamThreads) void stream_attention_kernel(
 #pragma unroll
     for (int e = 0; e < RHO; ++e)
         qc[e] = load_chunk<kBf16, EPL>(q_, (static_cast<size_t>(it.q_row0) * n_q_heads + head0 + e) * D + sub * EPL, true);
+
+    // Fused merge: the other part's values this thread will need in the epilogue are requested now,
+    // so their latency is hidden behind the whole KV stream.
+    //   WPI > 1: thread t of the item owns quads t, t + 64 WPI, ... of the item's RHO * D outputs;
+    //   WPI = 1: the 16-lane row g of the wavefront owns heads g, g + 4, ...; lane `sub` its EPL elements.
+    const size_t rh0 = static_cast<size_t>(it.q_row0) * n_q_heads + head0;   // (row, head) index of head 0
+    constexpr int kQuads = RHO * D / 4;
+    constexpr int kQuadsPerThread = WPI == 1 ? ((RHO + 3) / 4) * (EPL / 4) : (kQuads + 64 * WPI - 1) / (64 * WPI);
+    float4 pre_o[kQuadsPerThread];
+    float pre_l[kQuadsPerThread];
+    if (mt.o_a != nullptr && item_ok) {
+        if constexpr (WPI == 1) {
+#pragma unroll
+            for (int i = 0; i < (RHO + 3) / 4; ++i) {
+                const int e = 4 * i + (lane >> 4);
+                if (e < RHO) {
+#pragma unroll
+                    for (int x = 0; x < EPL / 4; ++x) {
+                        pre_o[i * (EPL / 4) + x] = *reinterpret_cast<const float4*>(mt.o_a + (rh0 + e) * D + sub * EPL + 4 * x);
+                        pre_l[i * (EPL / 4) + x] = mt.lse_a[rh0 + e];
+                    }
+                }
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < kQuadsPerThread; ++i) {
+                const int q4 = sw * 64 + lane + i * 64 * WPI;
+                if (q4 < kQuads) {
+                    pre_o[i] = *reinterpret_cast<const float4*>(mt.o_a + rh0 * D + 4 * q4);
+                    pre_l[i] = mt.lse_a[rh0 + (4 * q4) / D];
+                }
+            }
+        }
+    }
 
     float m[RHO], l[RHO], acc[RHO][EPL];
 #pragma unroll
@@ -377,7 +411,32 @@ __global__ __launch_bounds__(kStreamThreads) void stream_attention_kernel(
     }
 
     if constexpr (WPI == 1) {
-        if (item_ok && lane < 16) {
+        if (item_ok && mt.o_a != nullptr) {
+            // fused merge: this part is (acc / l, log-sum-exp) - every lane holds all of it after the
+            // exchange above - and the other part was requested at the start of the kernel
+#pragma unroll
+            for (int i = 0; i < (RHO + 3) / 4; ++i) {
+#pragma unroll
+                for (int ee = 0; ee < 4; ++ee) {
+                    const int e = 4 * i + ee;
+                    if (e < RHO && ee == (lane >> 4)) {
+                        const float inv = l[e] > 0.f ? 1.f / l[e] : 0.f;
+                        const float lb = l[e] > 0.f ? (m[e] * c2 + log2f(l[e])) * kLn2 : -INFINITY;
+                        const MergeWeights w = merge_weights(pre_l[i * (EPL / 4)], lb);
+                        const size_t off = (rh0 + e) * D + sub * EPL;
+#pragma unroll
+                        for (int x = 0; x < EPL; x += 4) {
+                            const float4 a = pre_o[i * (EPL / 4) + x / 4];
+                            store_out4<kBf16>(mt.o_out, off + x, merge_value(w, a.x, acc[e][x] * inv),
+                                              merge_value(w, a.y, acc[e][x + 1] * inv),
+                                              merge_value(w, a.z, acc[e][x + 2] * inv),
+                                              merge_value(w, a.w, acc[e][x + 3] * inv));
+                        }
+                        if (sub == 0 && mt.lse_out != nullptr) mt.lse_out[rh0 + e] = w.lse;
+                    }
+                }
+            }
+        } else if (item_ok && lane < 16) {
 #pragma unroll
             for (int e = 0; e < RHO; ++e) {
                 const float inv = l[e] > 0.f ? 1.f / l[e] : 0.f;     // empty range: output 0
@@ -401,7 +460,41 @@ __global__ __launch_bounds__(kStreamThreads) void stream_attention_kernel(
             }
         }
         __syncthreads();
-        if (item_ok) {
+        if (item_ok && mt.o_a != nullptr) {
+            // fused merge, four consecutive head-dim elements per thread; the other part's values were
+            // requested at the start of the kernel
+#pragma unroll
+            for (int i = 0; i < kQuadsPerThread; ++i) {
+                const int q4 = sw * 64 + lane + i * 64 * WPI;
+                if (q4 < kQuads) {
+                    const int e = (4 * q4) / D;
+                    const int d = 4 * q4 - e * D;
+                    float top = -INFINITY;
+#pragma unroll
+                    for (int w = 0; w < WPI; ++w) top = fmaxf(top, sm_m[item_in_block][w][e]);
+                    float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
+                    float den = 0.f;
+#pragma unroll
+                    for (int w = 0; w < WPI; ++w) {
+                        const float wgt = rel_weight<kPrecise>(sm_m[item_in_block][w][e], top, c2);
+                        const float4 x = *reinterpret_cast<const float4*>(&sm_acc[item_in_block][w][e][d]);
+                        num.x = fmaf(wgt, x.x, num.x);
+                        num.y = fmaf(wgt, x.y, num.y);
+                        num.z = fmaf(wgt, x.z, num.z);
+                        num.w = fmaf(wgt, x.w, num.w);
+                        den = fmaf(wgt, sm_l[item_in_block][w][e], den);
+                    }
+                    const float inv = den > 0.f ? 1.f / den : 0.f;
+                    const float lb = den > 0.f ? (top * c2 + log2f(den)) * kLn2 : -INFINITY;
+                    const MergeWeights mw = merge_weights(pre_l[i], lb);
+                    const float4 a = pre_o[i];
+                    store_out4<kBf16>(mt.o_out, (rh0 + e) * D + d, merge_value(mw, a.x, num.x * inv),
+                                      merge_value(mw, a.y, num.y * inv), merge_value(mw, a.z, num.z * inv),
+                                      merge_value(mw, a.w, num.w * inv));
+                    if (d == 0 && mt.lse_out != nullptr) mt.lse_out[rh0 + e] = mw.lse;
+                }
+            }
+        } else if (item_ok) {
             const int t_in_item = sw * 64 + lane;
             for (int idx = t_in_item; idx < RHO * D; idx += 64 * WPI) {
                 const int e = idx / D;
@@ -425,12 +518,12 @@ __global__ __launch_bounds__(kStreamThreads) void stream_attention_kernel(
 
 template <bool kBf16, int D, int RHO>
 hipError_t launch_wpi(const LaunchCtx& c, const Item* items, int32_t n_items, int wpi, const void* q, const void* k,
-                      const void* v, float* o_part, float* lse_part, float* ws_o, float* ws_lse) {
+                      const void* v, float* o_part, float* lse_part, float* ws_o, float* ws_lse, const MergeTarget& mt) {
     dim3 block(kStreamThreads);
 #define BLLM_LAUNCH_STREAM(W)                                                                                         \
     hipLaunchKernelGGL((stream_attention_kernel<kBf16, D, RHO, W>), dim3((n_items * W + 3) / 4), block, 0, c.stream,  \
                        items, n_items, q, k, v, o_part, lse_part, ws_o, ws_lse, c.desc->n_q_heads,                     \
-                       c.desc->n_kv_heads, c.scale)
+                       c.desc->n_kv_heads, c.scale, mt)
     switch (wpi) {
         case 1: BLLM_LAUNCH_STREAM(1); break;
         case 2: BLLM_LAUNCH_STREAM(2); break;
@@ -442,12 +535,12 @@ hipError_t launch_wpi(const LaunchCtx& c, const Item* items, int32_t n_items, in
 
 template <bool kBf16, int D>
 hipError_t launch_rho(const LaunchCtx& c, const Item* items, int32_t n_items, int wpi, const void* q, const void* k,
-                      const void* v, float* o_part, float* lse_part, float* ws_o, float* ws_lse) {
+                      const void* v, float* o_part, float* lse_part, float* ws_o, float* ws_lse, const MergeTarget& mt) {
     switch (c.desc->n_q_heads / c.desc->n_kv_heads) {
-        case 1: return launch_wpi<kBf16, D, 1>(c, items, n_items, wpi, q, k, v, o_part, lse_part, ws_o, ws_lse);
-        case 2: return launch_wpi<kBf16, D, 2>(c, items, n_items, wpi, q, k, v, o_part, lse_part, ws_o, ws_lse);
-        case 4: return launch_wpi<kBf16, D, 4>(c, items, n_items, wpi, q, k, v, o_part, lse_part, ws_o, ws_lse);
-        case 8: return launch_wpi<kBf16, D, 8>(c, items, n_items, wpi, q, k, v, o_part, lse_part, ws_o, ws_lse);
+        case 1: return launch_wpi<kBf16, D, 1>(c, items, n_items, wpi, q, k, v, o_part, lse_part, ws_o, ws_lse, mt);
+        case 2: return launch_wpi<kBf16, D, 2>(c, items, n_items, wpi, q, k, v, o_part, lse_part, ws_o, ws_lse, mt);
+        case 4: return launch_wpi<kBf16, D, 4>(c, items, n_items, wpi, q, k, v, o_part, lse_part, ws_o, ws_lse, mt);
+        case 8: return launch_wpi<kBf16, D, 8>(c, items, n_items, wpi, q, k, v, o_part, lse_part, ws_o, ws_lse, mt);
         default: return hipErrorInvalidValue;
     }
 }
@@ -456,15 +549,15 @@ hipError_t launch_rho(const LaunchCtx& c, const Item* items, int32_t n_items, in
 
 hipError_t launch_stream_attention(const LaunchCtx& c, const Item* items, int32_t n_items, int waves_per_item,
                                    const void* q, const void* k, const void* v, float* o_part, float* lse_part,
-                                   float* ws_o, float* ws_lse) {
+                                   float* ws_o, float* ws_lse, const MergeTarget& mt) {
     if (n_items <= 0) return hipSuccess;
     const bool bf16 = c.desc->dtype == BLLM_BF16;
     const int d = c.desc->head_dim;
     const int w = waves_per_item;
-    if (bf16 && d == 128) return launch_rho<true, 128>(c, items, n_items, w, q, k, v, o_part, lse_part, ws_o, ws_lse);
-    if (bf16 && d == 64) return launch_rho<true, 64>(c, items, n_items, w, q, k, v, o_part, lse_part, ws_o, ws_lse);
-    if (!bf16 && d == 128) return launch_rho<false, 128>(c, items, n_items, w, q, k, v, o_part, lse_part, ws_o, ws_lse);
-    if (!bf16 && d == 64) return launch_rho<false, 64>(c, items, n_items, w, q, k, v, o_part, lse_part, ws_o, ws_lse);
+    if (bf16 && d == 128) return launch_rho<true, 128>(c, items, n_items, w, q, k, v, o_part, lse_part, ws_o, ws_lse, mt);
+    if (bf16 && d == 64) return launch_rho<true, 64>(c, items, n_items, w, q, k, v, o_part, lse_part, ws_o, ws_lse, mt);
+    if (!bf16 && d == 128) return launch_rho<false, 128>(c, items, n_items, w, q, k, v, o_part, lse_part, ws_o, ws_lse, mt);
+    if (!bf16 && d == 64) return launch_rho<false, 64>(c, items, n_items, w, q, k, v, o_part, lse_part, ws_o, ws_lse, mt);
     return hipErrorInvalidValue;
 }
 

@@ -84,7 +84,7 @@ template <int NW, int BN>
 __global__ __launch_bounds__(64 * NW, 2) void tile_attention_kernel(
     const Item* __restrict__ items, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const uint16_t* __restrict__ v, float* __restrict__ o_part, float* __restrict__ lse_part, float* __restrict__ ws_o,
-    float* __restrict__ ws_lse, int n_q_heads, int n_kv_heads, int log2_rho, float scale) {
+    float* __restrict__ ws_lse, int n_q_heads, int n_kv_heads, int log2_rho, float scale, MergeTarget mt) {
     constexpr int kBN = BN;
     constexpr int kKvb = BN / 32;                    // 32-row blocks of S^T per step
     constexpr int kTileBytes = kBN * kRowBytes;
@@ -123,6 +123,20 @@ __global__ __launch_bounds__(64 * NW, 2) void tile_attention_kernel(
     const bool row_ok = tok < it.n_rows;
     const int vis = (row_ok && it.vis0 + tok < kv_len) ? it.vis0 + tok : kv_len;   // padding rows see everything
 
+    // (row, head) index of this lane's query in the [n_rows, Hq] arrays of a fused merge
+    const size_t rh = static_cast<size_t>(it.q_row0 + tok) * n_q_heads + head0 + hd;
+    if (kv_len <= 0 && mt.o_a != nullptr) {      // empty part, fused merge: the other part passes through
+        if (row_ok) {
+            const MergeWeights w = merge_weights(mt.lse_a[rh], -INFINITY);
+            for (int x = h * 64; x < h * 64 + 64; x += 4) {
+                const float4 a = *reinterpret_cast<const float4*>(mt.o_a + rh * kD + x);
+                store_out4<true>(mt.o_out, rh * kD + x, merge_value(w, a.x, 0.f), merge_value(w, a.y, 0.f),
+                                 merge_value(w, a.z, 0.f), merge_value(w, a.w, 0.f));
+            }
+            if (h == 0 && mt.lse_out != nullptr) mt.lse_out[rh] = w.lse;
+        }
+        return;
+    }
     if (kv_len <= 0) {               // empty part: output 0, log-sum-exp -inf
         if (row_ok) {
             float* orow = dst_o + (static_cast<size_t>(tok) * n_q_heads + hd) * kD;
@@ -345,7 +359,22 @@ __global__ __launch_bounds__(64 * NW, 2) void tile_attention_kernel(
 
     // ---- epilogue: normalise and store O (transposed back), log-sum-exp --------------------------
     const float ltot = l_run + __shfl_xor(l_run, 32);
-    if (row_ok) {
+    if (row_ok && mt.o_a != nullptr) {
+        // fused merge: this part is (O / l, log-sum-exp), the other part's row comes from memory
+        const float inv = 1.f / ltot;
+        const MergeWeights w = merge_weights(mt.lse_a[rh], (m_run + log2f(ltot)) * kLn2);
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const size_t off = rh * kD + 32 * db + 8 * i + 4 * h;
+                const float4 a = *reinterpret_cast<const float4*>(mt.o_a + off);
+                store_out4<true>(mt.o_out, off, merge_value(w, a.x, oacc[db][4 * i] * inv),
+                                 merge_value(w, a.y, oacc[db][4 * i + 1] * inv), merge_value(w, a.z, oacc[db][4 * i + 2] * inv),
+                                 merge_value(w, a.w, oacc[db][4 * i + 3] * inv));
+            }
+        if (h == 0 && mt.lse_out != nullptr) mt.lse_out[rh] = w.lse;
+    } else if (row_ok) {
         const float inv = 1.f / ltot;
         float* orow = dst_o + (static_cast<size_t>(tok) * n_q_heads + hd) * kD;
 #pragma unroll
@@ -365,7 +394,7 @@ __global__ __launch_bounds__(64 * NW, 2) void tile_attention_kernel(
 
 hipError_t launch_tile_attention(const LaunchCtx& c, const Item* items, int32_t n_items, int waves, const void* q,
                                  const void* k, const void* v, float* o_part, float* lse_part, float* ws_o,
-                                 float* ws_lse) {
+                                 float* ws_lse, const MergeTarget& mt) {
     if (n_items <= 0) return hipSuccess;
     if (c.desc->dtype != BLLM_BF16 || c.desc->head_dim != kD || waves != 4) return hipErrorInvalidValue;
     const int rho = c.desc->n_q_heads / c.desc->n_kv_heads;
@@ -376,7 +405,7 @@ hipError_t launch_tile_attention(const LaunchCtx& c, const Item* items, int32_t 
     const uint16_t* vv = static_cast<const uint16_t*>(v);
 #define BLLM_LAUNCH_TILE(NW_, BN_)                                                                                 \
     hipLaunchKernelGGL((tile_attention_kernel<NW_, BN_>), dim3(n_items), dim3(64 * NW_), 0, c.stream, items, qq, kk, vv, \
-                       o_part, lse_part, ws_o, ws_lse, c.desc->n_q_heads, c.desc->n_kv_heads, log2_rho, c.scale)
+                       o_part, lse_part, ws_o, ws_lse, c.desc->n_q_heads, c.desc->n_kv_heads, log2_rho, c.scale, mt)
     BLLM_LAUNCH_TILE(4, 64);
 #undef BLLM_LAUNCH_TILE
     return hipGetLastError();

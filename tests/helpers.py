@@ -1,5 +1,6 @@
 """Shared plumbing of the GPU parity tests: upload a seeded batch, run the three
-C-ABI calls, bring the results back in USER row order."""
+C-ABI calls (and the suffix pass that merges in its epilogue), bring the results back
+in USER row order."""
 import numpy as np
 
 import workload
@@ -34,14 +35,20 @@ def run_hip_path(batch, vals, scale=0.0, want_lse=True, pg=None):
     bllm.shared_prefix_attention(pg, q, kp, vp, o1, l1)
     bllm.suffix_attention(pg, q, ks, vs, o2, l2)
     bllm.lse_merge(pg, o1, l1, o2, l2, o, lse)
+    # the same final result through the suffix pass with the fused reduction
+    o_f = torch.full_like(o, nan)
+    lse_f = torch.full_like(l1, nan) if want_lse else None
+    bllm.suffix_attention_merged(pg, q, ks, vs, o1, l1, o_f, lse_f)
     torch.cuda.synchronize()
     inv = np.empty(T, dtype=np.int64)
     inv[meta["row_src"]] = np.arange(T)
     back = lambda t: t.float().cpu().numpy()[inv] if T > 0 else t.float().cpu().numpy()
     out = {"o": back(o), "o_prefix": back(o1), "lse_prefix": back(l1), "o_suffix": back(o2), "lse_suffix": back(l2),
            "meta": meta}
+    out["o_fused"] = back(o_f)
     if want_lse:
         out["lse"] = back(lse)
+        out["lse_fused"] = back(lse_f)
     if own:
         pg.destroy()
     return out

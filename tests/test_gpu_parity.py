@@ -4,7 +4,7 @@ import numpy as np
 import pytest
 
 import workload
-from helpers import TOL, max_abs_err, run_hip_path, run_oracle
+from helpers import TOL, layer_tuple, max_abs_err, run_hip_path, run_oracle
 
 pytestmark = pytest.mark.gpu
 
@@ -15,6 +15,9 @@ def check_all(batch, vals, scale=0.0, rows=None, requests=None):
     tol = TOL[batch.layer.dtype]
     errs = {k: max_abs_err(got[k], ref[k], rows) for k in
             ("o", "lse", "o_prefix", "lse_prefix", "o_suffix", "lse_suffix")}
+    # the two-call sequence (suffix pass with the reduction in its epilogue) against the same oracle values
+    errs["o_fused"] = max_abs_err(got["o_fused"], ref["o"], rows)
+    errs["lse_fused"] = max_abs_err(got["lse_fused"], ref["lse"], rows)
     print(batch.name, "T=%d" % batch.n_rows, {k: "%.2e" % v for k, v in errs.items()}, flush=True)
     # fp32 path: everything within 1e-5.  bf16 path: the merged output (rounded to bf16)
     # within 2e-2; the fp32 partial outputs within 1e-2 (the matrix-core P.V product rounds the
@@ -22,7 +25,7 @@ def check_all(batch, vals, scale=0.0, rows=None, requests=None):
     # log-sum-exp comes from fp32 scores of exact bf16 products and stays within 1e-4.
     bf16 = batch.layer.dtype == workload.BF16
     for k, v in errs.items():
-        bound = tol if k == "o" else (1e-4 if k.startswith("lse") else 1e-2) if bf16 else tol
+        bound = tol if k in ("o", "o_fused") else (1e-4 if k.startswith("lse") else 1e-2) if bf16 else tol
         assert v <= bound, (k, v, bound)
     return got, ref
 
@@ -113,6 +116,85 @@ def test_empty_batch_is_a_no_op():
     bllm.shared_prefix_attention(pg, None, None, None, None, None)
     bllm.suffix_attention(pg, None, None, None, None, None)
     bllm.lse_merge(pg, None, None, None, None, None)
+    bllm.suffix_attention_merged(pg, None, None, None, None, None, None)
+    pg.destroy()
+
+
+def test_fused_suffix_pass_drops_rows_of_an_empty_prefix_part():
+    """The suffix pass with the fused reduction on prefix partials whose log-sum-exp is -inf and
+    whose rows hold garbage: nothing of them may reach the output (decode rows and chunk rows)."""
+    import torch
+    import paper_2412_03594_amd as bllm
+    L = workload.Layer(8, 2, 128, workload.BF16)
+    b = workload.Batch("noprefix", L, np.zeros(2, np.int32), np.array([0, 1, 1], np.int32),
+                       np.array([1, 70, 5], np.int32), np.array([1, 70, 1], np.int32))
+    v = workload.draw_values(b, seed=4)
+    ref = run_oracle(b, v)
+    pg = bllm.prefix_group_create((8, 2, 128, workload.BF16, 0.0), b.prefix_len, b.req_group, b.req_suffix_len, b.req_q_len)
+    meta = pg.metadata()
+    T = meta["n_rows"]
+    dev = torch.device("cuda:0")
+    up = lambda x: torch.from_numpy(np.ascontiguousarray(x)).to(dev).to(torch.bfloat16).contiguous()
+    q, ks, vs = up(v["q"][meta["row_src"]]), up(v["k_suffix"]), up(v["v_suffix"])
+    o1 = torch.full((T, 8, 128), float("nan"), device=dev, dtype=torch.float32)
+    l1 = torch.full((T, 8), float("-inf"), device=dev, dtype=torch.float32)
+    o = torch.full((T, 8, 128), float("nan"), device=dev, dtype=torch.bfloat16)
+    lse = torch.full((T, 8), float("nan"), device=dev, dtype=torch.float32)
+    bllm.suffix_attention_merged(pg, q, ks, vs, o1, l1, o, lse)
+    torch.cuda.synchronize()
+    inv = np.empty(T, dtype=np.int64)
+    inv[meta["row_src"]] = np.arange(T)
+    assert max_abs_err(o.float().cpu().numpy()[inv], ref["o"]) <= TOL[workload.BF16]
+    assert max_abs_err(lse.cpu().numpy()[inv], ref["lse"]) <= 1e-4
+    pg.destroy()
+
+
+def test_graph_replays_match_eager_launches():
+    """The device calls of a step captured in a HIP graph: every replay, with eager work and
+    synchronisation in between and with new contents in the same input tensors, gives bit for
+    bit what the eager calls give (both call sequences)."""
+    import torch
+    import paper_2412_03594_amd as bllm
+    b = workload.ragged_toy(7, dtype=workload.BF16, n_q_heads=8, n_kv_heads=2, head_dim=128,
+                            n_groups=3, max_prefix=700, max_group=5, max_suffix=150, max_chunk=90)
+    L = b.layer
+    pg = bllm.prefix_group_create(layer_tuple(L), b.prefix_len, b.req_group, b.req_suffix_len, b.req_q_len)
+    meta = pg.metadata()
+    T = meta["n_rows"]
+    dev = torch.device("cuda:0")
+    up = lambda x: torch.from_numpy(np.ascontiguousarray(x)).to(dev).to(torch.bfloat16).contiguous()
+    sets = []
+    for seed in (11, 12):
+        v = workload.draw_values(b, seed=seed)
+        sets.append([up(v["q"][meta["row_src"]]), up(v["k_prefix"]), up(v["v_prefix"]), up(v["k_suffix"]), up(v["v_suffix"])])
+    cur = [t.clone() for t in sets[0]]             # the tensors the graph is captured on
+    mk = lambda *shape, dt=torch.float32: torch.zeros(shape, device=dev, dtype=dt)
+    bufs = {"o1": mk(T, 8, 128), "l1": mk(T, 8), "o2": mk(T, 8, 128), "l2": mk(T, 8),
+            "o": mk(T, 8, 128, dt=torch.bfloat16), "lse": mk(T, 8)}
+    for fused in (False, True):
+        run = lambda: bllm.prefix_shared_attention(pg, cur[0], cur[1], cur[2], cur[3], cur[4], bufs, fused=fused)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            run()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            run()
+        for which in (0, 1, 0):
+            for dst, src in zip(cur, sets[which]):
+                dst.copy_(src)
+            run()                                   # eager
+            torch.cuda.synchronize()
+            want_o, want_l = bufs["o"].clone(), bufs["lse"].clone()
+            bufs["o"].zero_()
+            bufs["lse"].zero_()
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(bufs["o"], want_o) and torch.equal(bufs["lse"], want_l), (fused, which)
+        del g
     pg.destroy()
 
 
