@@ -26,9 +26,9 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 # HBM bytes per launch of each pass, from rocprofv3 FETCH_SIZE + WRITE_SIZE runs scaled by a plain
 # copy of known size (the summaries and commands are under profiles/<workload>_kernels.md).
 MEASURED_TRAFFIC_BYTES = {
-    "l8b_decode": {"suffix": 306.8e6, "prefix": 108.5e6, "merge": 10.8e6},
-    "rank_longprefix": {"suffix": 331.8e6, "prefix": 229.9e6, "merge": 43.0e6},
-    "l8b_mixed": {"suffix": 824.5e6, "prefix": 668.6e6, "merge": 709.4e6},
+    "l8b_decode": {"suffix": 306.8e6, "prefix": 108.0e6, "merge": 10.8e6, "suffix_merged": 309.2e6},
+    "rank_longprefix": {"suffix": 331.8e6, "prefix": 228.6e6, "merge": 43.0e6, "suffix_merged": 340.3e6},
+    "l8b_mixed": {"suffix": 823.5e6, "prefix": 664.6e6, "merge": 709.4e6, "suffix_merged": 989.9e6},
 }
 
 
