@@ -110,7 +110,7 @@ def oracle_baseline(batch, vals, budget_s=15.0):
                       (done_reqs, len(order), len(by_group), done_rows, dt)}
 
 
-def run_workload(name, steps, warmup, seed, rotate, torch, bllm, workload, with_values_host=True, schedule="fused",
+def run_workload(name, steps, warmup, seed, rotate, torch, bllm, workload, with_values_host=True, schedule="one_call",
                  use_graph=False):
     batch = workload.CONFIGS[name](seed)
     L = batch.layer
@@ -178,7 +178,13 @@ def run_workload(name, steps, warmup, seed, rotate, torch, bllm, workload, with_
         bllm.shared_prefix_attention(pg, q, b[0], b[1], o1, l1)
         bllm.suffix_attention_merged(pg, q, b[2], b[3], o1, l1, o, None)
 
-    step = step_fused if schedule == "fused" else step_three_call
+    ws = torch.empty(bllm.prefix_shared_workspace_bytes(pg) // 4 + 1, device=dev, dtype=torch.float32)
+
+    def step_one_call():
+        b = nxt()
+        bllm.prefix_shared_attention(pg, q, b[0], b[1], b[2], b[3], ws, o, None)
+
+    step = {"one_call": step_one_call, "fused": step_fused, "three_call": step_three_call}[schedule]
 
     # One captured HIP graph per KV copy: a replay is exactly one step; the launches of a step reach
     # the GPU as one submission, without per-kernel launch gaps.
@@ -237,7 +243,7 @@ def run_workload(name, steps, warmup, seed, rotate, torch, bllm, workload, with_
 def roofline_of(res):
     """Roofline record of the pass that takes the most time."""
     t = res["t_pass"]
-    in_step = ("prefix", "suffix_merged") if res["schedule"] == "fused" else ("prefix", "suffix", "merge")
+    in_step = ("prefix", "suffix", "merge") if res["schedule"] == "three_call" else ("prefix", "suffix_merged")
     name = max(in_step, key=lambda k: t[k])
     traffic = MEASURED_TRAFFIC_BYTES.get(res["batch"].name, {}).get(name)
     w = res["work"][name]
@@ -267,9 +273,11 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--rotate", type=int, default=0,
                     help="copies of the KV tensors cycled through (0: enough to defeat the Infinity Cache, 2..16)")
-    ap.add_argument("--schedule", choices=["fused", "three_call"], default="fused",
-                    help="timed step: prefix pass + suffix pass with the reduction in its epilogue (two calls), "
-                         "or prefix, suffix and merge passes (three calls); both give the same final output")
+    ap.add_argument("--schedule", choices=["one_call", "fused", "three_call"], default="one_call",
+                    help="timed step: the one-call entry point (prefix kernels, then suffix kernels that fold the prefix "
+                         "result - split pieces included - in their epilogue); prefix pass + suffix pass with the "
+                         "reduction in its epilogue (two calls); or prefix, suffix and merge passes (three calls).  "
+                         "All give the same final output")
     ap.add_argument("--graph", action="store_true",
                     help="replay one captured HIP graph per timed step instead of launching eagerly (measured slower "
                          "than eager launches on the decode workload, faster on the long-running ones)")

@@ -35,6 +35,7 @@
 #ifndef BLLM_H
 #define BLLM_H
 
+#include <stddef.h>
 #include <stdint.h>
 
 #ifdef __cplusplus
@@ -189,6 +190,30 @@ int bllm_lse_merge(const bllm_prefix_groups* pg,
 int bllm_suffix_attention_merged(const bllm_prefix_groups* pg, const void* q,
                                  const void* k_suffix, const void* v_suffix,
                                  const float* o_prefix, const float* lse_prefix,
+                                 void* o_out, float* lse_out, void* hip_stream);
+
+/* The whole path in one call (Sec. 4.3.3: the partial attention on the shared
+ * context and on the distinct part, Sec. 5: reduced through online softmax):
+ * shared-prefix kernels, then the distinct-suffix kernels, which fold the
+ * prefix result of every row into their own in their epilogue and write the
+ * final output.  No separate reduction launch; a prefix that was split along
+ * KV for occupancy is folded piece by piece, without a combine launch either.
+ * The result equals the three-call sequence up to fp32 rounding.
+ *   q, k_prefix, v_prefix, k_suffix, v_suffix   as for the single passes
+ *   workspace        device, 16-byte aligned, at least
+ *                    bllm_prefix_shared_workspace_bytes(pg) bytes; holds the
+ *                    prefix partial between the two groups of kernels; owned by
+ *                    the caller, contents undefined afterwards, may be reused by
+ *                    the next call on the same stream
+ *   o_out            device [T,Hq,D] desc.dtype   every element written
+ *   lse_out          device [T,Hq] fp32, or NULL
+ * Errors as the other device calls (BLLM_INVALID_ARG for a small or misaligned
+ * workspace).  Allocates nothing. */
+size_t bllm_prefix_shared_workspace_bytes(const bllm_prefix_groups* pg);
+int bllm_prefix_shared_attention(const bllm_prefix_groups* pg, const void* q,
+                                 const void* k_prefix, const void* v_prefix,
+                                 const void* k_suffix, const void* v_suffix,
+                                 void* workspace, size_t workspace_bytes,
                                  void* o_out, float* lse_out, void* hip_stream);
 
 const char* bllm_last_error(void);

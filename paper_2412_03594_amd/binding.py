@@ -14,7 +14,8 @@ _LIB = None
 
 EXPORTS = ["bllm_prefix_group_create", "bllm_prefix_group_create_host", "bllm_prefix_group_metadata",
            "bllm_prefix_group_destroy", "bllm_shared_prefix_attention", "bllm_suffix_attention", "bllm_lse_merge",
-           "bllm_suffix_attention_merged", "bllm_last_error", "bllm_version"]
+           "bllm_suffix_attention_merged", "bllm_prefix_shared_attention", "bllm_prefix_shared_workspace_bytes",
+           "bllm_last_error", "bllm_version"]
 
 
 class BllmError(RuntimeError):
@@ -72,7 +73,11 @@ def load_library():
                                    C.c_void_p]
     lib.bllm_suffix_attention_merged.argtypes = [h, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                                  C.c_void_p, C.c_void_p, C.c_void_p]
-    for name in EXPORTS[:8]:
+    lib.bllm_prefix_shared_attention.argtypes = [h, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                                 C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.bllm_prefix_shared_workspace_bytes.argtypes = [h]
+    lib.bllm_prefix_shared_workspace_bytes.restype = C.c_size_t
+    for name in EXPORTS[:9]:
         getattr(lib, name).restype = C.c_int
     lib.bllm_last_error.restype = C.c_char_p
     lib.bllm_version.restype = C.c_char_p
@@ -204,8 +209,21 @@ def lse_merge(pg, o_a, lse_a, o_b, lse_b, o_out, lse_out=None, stream=None):
                                          _ptr(lse_out), _stream(stream)))
 
 
-def prefix_shared_attention(pg, q, k_prefix, v_prefix, k_suffix, v_suffix, bufs, stream=None, fused=False):
-    """The device calls of the path in sequence on one stream.  bufs: dict with preallocated
+def prefix_shared_workspace_bytes(pg):
+    return int(load_library().bllm_prefix_shared_workspace_bytes(pg.handle))
+
+
+def prefix_shared_attention(pg, q, k_prefix, v_prefix, k_suffix, v_suffix, workspace, o_out, lse_out=None, stream=None):
+    """The whole path in one call; `workspace` is a device tensor of at least
+    prefix_shared_workspace_bytes(pg) bytes."""
+    nbytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(load_library().bllm_prefix_shared_attention(pg.handle, _ptr(q), _ptr(k_prefix), _ptr(v_prefix), _ptr(k_suffix),
+                                                       _ptr(v_suffix), _ptr(workspace), nbytes, _ptr(o_out),
+                                                       _ptr(lse_out), _stream(stream)))
+
+
+def three_call_attention(pg, q, k_prefix, v_prefix, k_suffix, v_suffix, bufs, stream=None, fused=False):
+    """The single-pass device calls in sequence on one stream.  bufs: dict with preallocated
     o1, l1 (fp32 partials of the prefix pass), o (layer dtype), optionally lse, and - for the
     three-call sequence - o2, l2 (fp32 partials of the suffix pass).  fused=True uses the suffix
     pass that merges in its epilogue (two calls, no o2 / l2)."""

@@ -239,19 +239,12 @@ int bllm_prefix_group_destroy(bllm_prefix_groups* pg) {
     return rc;
 }
 
-// One attention pass.  With a merge target the pass writes the merged final output instead of
-// its own partial (o_part / lse_part are then unused).
-static int run_pass(const bllm_prefix_groups* pg, bool prefix, const void* q, const void* k, const void* v,
-                    float* o_part, float* lse_part, const MergeTarget& mt, void* hip_stream) {
-    const bool fused = mt.o_a != nullptr;
-    int rc = fused ? check_device_call(pg, {q, mt.o_a, mt.lse_a, mt.o_out}) : check_device_call(pg, {q, o_part, lse_part});
-    if (rc != BLLM_OK) return rc;
+// The attention kernels of one pass (matrix-core tiles, then streaming items), without the
+// combine of split KV ranges.  With a merge target they write the merged final output instead
+// of the pass's own partial (o_part / lse_part are then unused).
+static int launch_pass_kernels(const bllm_prefix_groups* pg, bool prefix, const void* q, const void* k, const void* v,
+                               float* o_part, float* lse_part, const MergeTarget& mt, void* hip_stream) {
     const Packing& p = pg->pk;
-    if (fused && (prefix ? p.prefix_has_split : p.suffix_has_split)) {
-        set_error("a pass whose KV ranges are split cannot merge in its epilogue");
-        return BLLM_UNSUPPORTED;
-    }
-    if (p.n_rows == 0) return BLLM_OK;
     const auto& tiles = prefix ? p.prefix_tile_items : p.suffix_tile_items;
     const auto& rows = prefix ? p.prefix_row_items : p.suffix_row_items;
     const int64_t kv_rows = prefix ? p.prefix_kv_start.back() : p.req_kv_start.back();
@@ -273,9 +266,27 @@ static int run_pass(const bllm_prefix_groups* pg, bool prefix, const void* q, co
                                     o_part, lse_part, pg->d.ws_o, pg->d.ws_lse, mt);
         if (e != hipSuccess) return hip_fail(e, "streaming attention launch");
     }
+    return BLLM_OK;
+}
+
+// One attention pass as an entry point sees it: kernels, then the combine of split KV ranges.
+static int run_pass(const bllm_prefix_groups* pg, bool prefix, const void* q, const void* k, const void* v,
+                    float* o_part, float* lse_part, const MergeTarget& mt, void* hip_stream) {
+    const bool fused = mt.o_a != nullptr;
+    int rc = fused ? check_device_call(pg, {q, mt.o_a, mt.lse_a, mt.o_out}) : check_device_call(pg, {q, o_part, lse_part});
+    if (rc != BLLM_OK) return rc;
+    const Packing& p = pg->pk;
+    if (fused && (prefix ? p.prefix_has_split : p.suffix_has_split)) {
+        set_error("a pass whose KV ranges are split cannot merge in its epilogue");
+        return BLLM_UNSUPPORTED;
+    }
+    if (p.n_rows == 0) return BLLM_OK;
+    rc = launch_pass_kernels(pg, prefix, q, k, v, o_part, lse_part, mt, hip_stream);
+    if (rc != BLLM_OK) return rc;
     if (prefix ? p.prefix_has_split : p.suffix_has_split) {
-        e = launch_split_combine(c, prefix ? pg->d.prefix_row_split : pg->d.suffix_row_split, pg->d.ws_o, pg->d.ws_lse,
-                                 o_part, lse_part);
+        LaunchCtx c = make_ctx(pg, hip_stream);
+        hipError_t e = launch_split_combine(c, prefix ? pg->d.prefix_row_split : pg->d.suffix_row_split, pg->d.ws_o,
+                                            pg->d.ws_lse, o_part, lse_part);
         if (e != hipSuccess) return hip_fail(e, "split combine launch");
     }
     return BLLM_OK;
@@ -315,6 +326,48 @@ int bllm_lse_merge(const bllm_prefix_groups* pg, const float* o_a, const float* 
     hipError_t e = launch_lse_merge(c, o_a, lse_a, o_b, lse_b, o_out, lse_out);
     if (e != hipSuccess) return hip_fail(e, "lse merge launch");
     return BLLM_OK;
+}
+
+size_t bllm_prefix_shared_workspace_bytes(const bllm_prefix_groups* pg) {
+    if (!pg) return 0;
+    const size_t row_heads = static_cast<size_t>(pg->pk.n_rows) * pg->desc.n_q_heads;
+    return align256(row_heads * pg->desc.head_dim * sizeof(float)) + align256(row_heads * sizeof(float));
+}
+
+int bllm_prefix_shared_attention(const bllm_prefix_groups* pg, const void* q, const void* k_prefix, const void* v_prefix,
+                                 const void* k_suffix, const void* v_suffix, void* workspace, size_t workspace_bytes,
+                                 void* o_out, float* lse_out, void* hip_stream) {
+    int rc = check_device_call(pg, {q, workspace, o_out});
+    if (rc != BLLM_OK) return rc;
+    const Packing& p = pg->pk;
+    if (p.n_rows == 0) return BLLM_OK;
+    if (workspace_bytes < bllm_prefix_shared_workspace_bytes(pg) || (reinterpret_cast<uintptr_t>(workspace) & 15) != 0) {
+        set_error("workspace too small (see bllm_prefix_shared_workspace_bytes) or not 16-byte aligned");
+        return BLLM_INVALID_ARG;
+    }
+    if (p.suffix_has_split) {
+        set_error("a pass whose KV ranges are split cannot merge in its epilogue");
+        return BLLM_UNSUPPORTED;
+    }
+    // prefix partial of the rows whose prefix range is not split: [T, Hq, D] then [T, Hq]
+    const size_t row_heads = static_cast<size_t>(p.n_rows) * pg->desc.n_q_heads;
+    float* o1 = static_cast<float*>(workspace);
+    float* l1 = reinterpret_cast<float*>(static_cast<char*>(workspace) + align256(row_heads * pg->desc.head_dim * sizeof(float)));
+    rc = launch_pass_kernels(pg, true, q, k_prefix, v_prefix, o1, l1, MergeTarget{}, hip_stream);
+    if (rc != BLLM_OK) return rc;
+    // The suffix kernels fold every prefix partial of a row - one, or the pieces of a split prefix
+    // straight from the split workspace, without a combine launch - with their own result.
+    MergeTarget mt;
+    mt.o_a = o1;
+    mt.lse_a = l1;
+    mt.o_out = o_out;
+    mt.lse_out = lse_out;
+    if (p.prefix_has_split) {
+        mt.row_split = pg->d.prefix_row_split;
+        mt.ws_o = pg->d.ws_o;
+        mt.ws_lse = pg->d.ws_lse;
+    }
+    return launch_pass_kernels(pg, false, q, k_suffix, v_suffix, nullptr, nullptr, mt, hip_stream);
 }
 
 const char* bllm_last_error(void) { return g_last_error.c_str(); }

@@ -53,6 +53,33 @@ __device__ __forceinline__ MergeWeights merge_weights(float la, float lb) {
 __device__ __forceinline__ float merge_value(const MergeWeights& w, float a, float b) {
     return (w.wa * (w.wa > 0.f ? a : 0.f) + w.wb * (w.wb > 0.f ? b : 0.f)) * w.inv;
 }
+// Running online-softmax fold of any number of normalised partial results, four consecutive
+// elements at a time: (top, den, num) with result num / den and log-sum-exp top + log(den).
+// A partial with log-sum-exp -inf is skipped (its values are never touched).
+struct PartialFold {
+    float top = -INFINITY;
+    float den = 0.f;
+    float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
+};
+__device__ __forceinline__ void fold_add(PartialFold& f, float lse, const float4& x) {
+    if (lse == -INFINITY) return;
+    const float m = fmaxf(f.top, lse);
+    const float r = f.top == -INFINITY ? 0.f : expf(f.top - m);
+    const float w = expf(lse - m);
+    f.num.x = fmaf(w, x.x, f.num.x * r);
+    f.num.y = fmaf(w, x.y, f.num.y * r);
+    f.num.z = fmaf(w, x.z, f.num.z * r);
+    f.num.w = fmaf(w, x.w, f.num.w * r);
+    f.den = fmaf(f.den, r, w);
+    f.top = m;
+}
+// result of the fold: values in `o`, log-sum-exp returned (nothing folded: 0 and -inf)
+__device__ __forceinline__ float fold_result(const PartialFold& f, float4& o) {
+    const float inv = f.den > 0.f ? 1.f / f.den : 0.f;
+    o = make_float4(f.num.x * inv, f.num.y * inv, f.num.z * inv, f.num.w * inv);
+    return f.den > 0.f ? f.top + logf(f.den) : -INFINITY;
+}
+
 // Stores 4 consecutive merged elements at element offset `off` of an output in the layer's dtype.
 template <bool kBf16Out>
 __device__ __forceinline__ void store_out4(void* out, size_t off, float x0, float x1, float x2, float x3) {

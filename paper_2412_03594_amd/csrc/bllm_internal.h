@@ -94,6 +94,12 @@ struct MergeTarget {
     const float* lse_a = nullptr;  // [n_rows, Hq]
     void* o_out = nullptr;         // [n_rows, Hq, D] in the layer's dtype
     float* lse_out = nullptr;      // [n_rows, Hq] or null
+    // When row_split is not null the other part of packed row t may still be in pieces: with
+    // row_split[t].n_splits > 0 its partial c is workspace row ws_row0 + c * stride of (ws_o, ws_lse)
+    // instead of row t of (o_a, lse_a); the kernel folds all of them.
+    const RowSplit* row_split = nullptr;
+    const float* ws_o = nullptr;
+    const float* ws_lse = nullptr;
 };
 
 hipError_t launch_stream_attention(const LaunchCtx& c, const Item* items, int32_t n_items, int waves_per_item,

@@ -116,7 +116,9 @@ __device__ __forceinline__ uint32_t row16_broadcast_u32(uint32_t x) {
     return static_cast<uint32_t>(__builtin_amdgcn_ds_swizzle(static_cast<int>(x), kPattern));
 }
 
-template <bool kBf16, int D, int RHO, int WPI>
+// kPieces: the other part of a fused merge may be in several pieces (a split prefix); without it the
+// kernel handles exactly one other partial and carries none of the bookkeeping.
+template <bool kBf16, int D, int RHO, int WPI, bool kPieces>
 __global__ __launch_bounds__(kStreamThreads) void stream_attention_kernel(
     const Item* __restrict__ items, int n_items, const void* __restrict__ q_, const void* __restrict__ k_,
     const void* __restrict__ v_, float* __restrict__ o_part, float* __restrict__ lse_part, float* __restrict__ ws_o,
@@ -160,39 +162,60 @@ __global__ __launch_bounds__(kStreamThreads) void stream_attention_kernel(
     for (int e = 0; e < RHO; ++e)
         qc[e] = load_chunk<kBf16, EPL>(q_, (static_cast<size_t>(it.q_row0) * n_q_heads + head0 + e) * D + sub * EPL, true);
 
-    // Fused merge: the other part's values this thread will need in the epilogue are requested now,
-    // so their latency is hidden behind the whole KV stream.
+    // Fused merge: the other part of this item's row may be one partial result (row q_row0 of
+    // mt.o_a / mt.lse_a) or n_other partial results in the split workspace.  What this thread will
+    // need of them in the epilogue is requested right after the first K/V loads (up to kPre partials
+    // per owned quad), so the latency is hidden behind the whole KV stream.
     //   WPI > 1: thread t of the item owns quads t, t + 64 WPI, ... of the item's RHO * D outputs;
     //   WPI = 1: the 16-lane row g of the wavefront owns heads g, g + 4, ...; lane `sub` its EPL elements.
     const size_t rh0 = static_cast<size_t>(it.q_row0) * n_q_heads + head0;   // (row, head) index of head 0
     constexpr int kQuads = RHO * D / 4;
     constexpr int kQuadsPerThread = WPI == 1 ? ((RHO + 3) / 4) * (EPL / 4) : (kQuads + 64 * WPI - 1) / (64 * WPI);
-    float4 pre_o[kQuadsPerThread];
-    float pre_l[kQuadsPerThread];
-    if (mt.o_a != nullptr && item_ok) {
-        if constexpr (WPI == 1) {
-#pragma unroll
-            for (int i = 0; i < (RHO + 3) / 4; ++i) {
-                const int e = 4 * i + (lane >> 4);
-                if (e < RHO) {
-#pragma unroll
-                    for (int x = 0; x < EPL / 4; ++x) {
-                        pre_o[i * (EPL / 4) + x] = *reinterpret_cast<const float4*>(mt.o_a + (rh0 + e) * D + sub * EPL + 4 * x);
-                        pre_l[i * (EPL / 4) + x] = mt.lse_a[rh0 + e];
-                    }
-                }
-            }
-        } else {
-#pragma unroll
-            for (int i = 0; i < kQuadsPerThread; ++i) {
-                const int q4 = sw * 64 + lane + i * 64 * WPI;
-                if (q4 < kQuads) {
-                    pre_o[i] = *reinterpret_cast<const float4*>(mt.o_a + rh0 * D + 4 * q4);
-                    pre_l[i] = mt.lse_a[rh0 + (4 * q4) / D];
-                }
-            }
-        }
+    constexpr int kPre = !kPieces ? 1 : WPI == 1 ? 2 : 4;
+    const bool fused = mt.o_a != nullptr;
+    RowSplit sp{0, 0, 0};
+    if constexpr (kPieces) {
+        if (fused && mt.row_split != nullptr) sp = mt.row_split[it.q_row0];
     }
+    const int n_other = (kPieces && sp.n_splits > 0) ? sp.n_splits : 1;
+    // head e's partial c: D values at other_o(e, c), log-sum-exp other_l(e, c)
+    auto other_o = [&](int e, int c) -> const float* {
+        return (kPieces && sp.n_splits > 0)
+                   ? mt.ws_o + (static_cast<size_t>(sp.ws_row0 + c * sp.stride) * n_q_heads + head0 + e) * D
+                   : mt.o_a + (rh0 + e) * D;
+    };
+    auto other_l = [&](int e, int c) -> float {
+        return (kPieces && sp.n_splits > 0) ? mt.ws_lse[static_cast<size_t>(sp.ws_row0 + c * sp.stride) * n_q_heads + head0 + e]
+                               : mt.lse_a[rh0 + e];
+    };
+    // the quad with index i of this thread: head e, first element d (false: no such quad)
+    auto quad_of = [&](int i, int& e, int& d) -> bool {
+        if constexpr (WPI == 1) {
+            e = 4 * (i / (EPL / 4)) + (lane >> 4);
+            d = sub * EPL + 4 * (i % (EPL / 4));
+            return e < RHO;
+        } else {
+            const int q4 = sw * 64 + lane + i * 64 * WPI;
+            e = (4 * q4) / D;
+            d = 4 * q4 - e * D;
+            return q4 < kQuads;
+        }
+    };
+    float4 pre_o[kQuadsPerThread][kPre];
+    float pre_l[kQuadsPerThread][kPre];
+    // folds the other part's partials of quad i (head e, element d), then this part's (lb, o2); stores
+    auto fold_and_store = [&](int i, int e, int d, float lb, const float4& o2) {
+        PartialFold f;
+#pragma unroll
+        for (int c = 0; c < kPre; ++c)
+            if (c < n_other) fold_add(f, pre_l[i][c], pre_o[i][c]);
+        for (int c = kPre; c < n_other; ++c) fold_add(f, other_l(e, c), *reinterpret_cast<const float4*>(other_o(e, c) + d));
+        fold_add(f, lb, o2);
+        float4 r;
+        const float lse = fold_result(f, r);
+        store_out4<kBf16>(mt.o_out, (rh0 + e) * D + d, r.x, r.y, r.z, r.w);
+        if (d == 0 && mt.lse_out != nullptr) mt.lse_out[rh0 + e] = lse;
+    };
 
     float m[RHO], l[RHO], acc[RHO][EPL];
 #pragma unroll
@@ -356,9 +379,26 @@ __global__ __launch_bounds__(kStreamThreads) void stream_attention_kernel(
     // Software pipeline: the loads of step n+1 are in flight while step n computes.  The two
     // register buffers swap roles every step (no copies), and the last step is peeled so that
     // every prefetch inside the loop is unconditional.
-    if (stream < kv_len) {
+    const bool has_rows = stream < kv_len;
+    if (has_rows) fetch(stream, ka, va);
+    // The requests for the other part's partials go out behind the first K/V loads, so the K/V
+    // stream does not start later because of them (loads return in order).
+    if (fused && item_ok) {
+#pragma unroll
+        for (int i = 0; i < kQuadsPerThread; ++i) {
+            int e, d;
+            if (quad_of(i, e, d)) {
+#pragma unroll
+                for (int c = 0; c < kPre; ++c)
+                    if (c < n_other) {
+                        pre_o[i][c] = *reinterpret_cast<const float4*>(other_o(e, c) + d);
+                        pre_l[i][c] = other_l(e, c);
+                    }
+            }
+        }
+    }
+    if (has_rows) {
         int base = stream;
-        fetch(base, ka, va);
         for (;;) {
             if (base + kRowsPerIter >= kv_len) {
                 step(base, ka, va);
@@ -411,28 +451,21 @@ __global__ __launch_bounds__(kStreamThreads) void stream_attention_kernel(
     }
 
     if constexpr (WPI == 1) {
-        if (item_ok && mt.o_a != nullptr) {
-            // fused merge: this part is (acc / l, log-sum-exp) - every lane holds all of it after the
-            // exchange above - and the other part was requested at the start of the kernel
+        if (item_ok && fused) {
+            // fused merge: this part is (acc / l, log-sum-exp); every lane holds all of it after the
+            // exchange above
 #pragma unroll
-            for (int i = 0; i < (RHO + 3) / 4; ++i) {
+            for (int i = 0; i < kQuadsPerThread; ++i) {
 #pragma unroll
                 for (int ee = 0; ee < 4; ++ee) {
-                    const int e = 4 * i + ee;
+                    constexpr int kPerHead = EPL / 4;
+                    const int e = 4 * (i / kPerHead) + ee;          // static: indexes the register arrays
+                    const int x = 4 * (i % kPerHead);
                     if (e < RHO && ee == (lane >> 4)) {
                         const float inv = l[e] > 0.f ? 1.f / l[e] : 0.f;
                         const float lb = l[e] > 0.f ? (m[e] * c2 + log2f(l[e])) * kLn2 : -INFINITY;
-                        const MergeWeights w = merge_weights(pre_l[i * (EPL / 4)], lb);
-                        const size_t off = (rh0 + e) * D + sub * EPL;
-#pragma unroll
-                        for (int x = 0; x < EPL; x += 4) {
-                            const float4 a = pre_o[i * (EPL / 4) + x / 4];
-                            store_out4<kBf16>(mt.o_out, off + x, merge_value(w, a.x, acc[e][x] * inv),
-                                              merge_value(w, a.y, acc[e][x + 1] * inv),
-                                              merge_value(w, a.z, acc[e][x + 2] * inv),
-                                              merge_value(w, a.w, acc[e][x + 3] * inv));
-                        }
-                        if (sub == 0 && mt.lse_out != nullptr) mt.lse_out[rh0 + e] = w.lse;
+                        fold_and_store(i, e, sub * EPL + x, lb,
+                                       make_float4(acc[e][x] * inv, acc[e][x + 1] * inv, acc[e][x + 2] * inv, acc[e][x + 3] * inv));
                     }
                 }
             }
@@ -460,15 +493,12 @@ __global__ __launch_bounds__(kStreamThreads) void stream_attention_kernel(
             }
         }
         __syncthreads();
-        if (item_ok && mt.o_a != nullptr) {
-            // fused merge, four consecutive head-dim elements per thread; the other part's values were
-            // requested at the start of the kernel
+        if (item_ok && fused) {
+            // fused merge, four consecutive head-dim elements per thread
 #pragma unroll
             for (int i = 0; i < kQuadsPerThread; ++i) {
-                const int q4 = sw * 64 + lane + i * 64 * WPI;
-                if (q4 < kQuads) {
-                    const int e = (4 * q4) / D;
-                    const int d = 4 * q4 - e * D;
+                int e, d;
+                if (quad_of(i, e, d)) {
                     float top = -INFINITY;
 #pragma unroll
                     for (int w = 0; w < WPI; ++w) top = fmaxf(top, sm_m[item_in_block][w][e]);
@@ -486,12 +516,7 @@ __global__ __launch_bounds__(kStreamThreads) void stream_attention_kernel(
                     }
                     const float inv = den > 0.f ? 1.f / den : 0.f;
                     const float lb = den > 0.f ? (top * c2 + log2f(den)) * kLn2 : -INFINITY;
-                    const MergeWeights mw = merge_weights(pre_l[i], lb);
-                    const float4 a = pre_o[i];
-                    store_out4<kBf16>(mt.o_out, (rh0 + e) * D + d, merge_value(mw, a.x, num.x * inv),
-                                      merge_value(mw, a.y, num.y * inv), merge_value(mw, a.z, num.z * inv),
-                                      merge_value(mw, a.w, num.w * inv));
-                    if (d == 0 && mt.lse_out != nullptr) mt.lse_out[rh0 + e] = mw.lse;
+                    fold_and_store(i, e, d, lb, make_float4(num.x * inv, num.y * inv, num.z * inv, num.w * inv));
                 }
             }
         } else if (item_ok) {
@@ -520,16 +545,22 @@ template <bool kBf16, int D, int RHO>
 hipError_t launch_wpi(const LaunchCtx& c, const Item* items, int32_t n_items, int wpi, const void* q, const void* k,
                       const void* v, float* o_part, float* lse_part, float* ws_o, float* ws_lse, const MergeTarget& mt) {
     dim3 block(kStreamThreads);
-#define BLLM_LAUNCH_STREAM(W)                                                                                         \
-    hipLaunchKernelGGL((stream_attention_kernel<kBf16, D, RHO, W>), dim3((n_items * W + 3) / 4), block, 0, c.stream,  \
-                       items, n_items, q, k, v, o_part, lse_part, ws_o, ws_lse, c.desc->n_q_heads,                     \
+#define BLLM_LAUNCH_STREAM_P(W, P)                                                                                    \
+    hipLaunchKernelGGL((stream_attention_kernel<kBf16, D, RHO, W, P>), dim3((n_items * W + 3) / 4), block, 0,        \
+                       c.stream, items, n_items, q, k, v, o_part, lse_part, ws_o, ws_lse, c.desc->n_q_heads,           \
                        c.desc->n_kv_heads, c.scale, mt)
+#define BLLM_LAUNCH_STREAM(W)                                                                                         \
+    do {                                                                                                              \
+        if (mt.row_split != nullptr) BLLM_LAUNCH_STREAM_P(W, true);                                                   \
+        else BLLM_LAUNCH_STREAM_P(W, false);                                                                          \
+    } while (0)
     switch (wpi) {
         case 1: BLLM_LAUNCH_STREAM(1); break;
         case 2: BLLM_LAUNCH_STREAM(2); break;
         default: BLLM_LAUNCH_STREAM(4); break;
     }
 #undef BLLM_LAUNCH_STREAM
+#undef BLLM_LAUNCH_STREAM_P
     return hipGetLastError();
 }
 

@@ -125,15 +125,34 @@ __global__ __launch_bounds__(64 * NW, 2) void tile_attention_kernel(
 
     // (row, head) index of this lane's query in the [n_rows, Hq] arrays of a fused merge
     const size_t rh = static_cast<size_t>(it.q_row0 + tok) * n_q_heads + head0 + hd;
+    // Fused merge: the other part of this lane's row is one partial result (row of mt.o_a / mt.lse_a)
+    // or, for a row with split KV ranges, n_other partial results in the split workspace.
+    RowSplit sp{0, 0, 0};
+    if (mt.o_a != nullptr && mt.row_split != nullptr && row_ok) sp = mt.row_split[it.q_row0 + tok];
+    const int n_other = sp.n_splits > 0 ? sp.n_splits : 1;
+    auto other_o = [&](int c) -> const float* {
+        return sp.n_splits > 0 ? mt.ws_o + (static_cast<size_t>(sp.ws_row0 + c * sp.stride) * n_q_heads + head0 + hd) * kD
+                               : mt.o_a + rh * kD;
+    };
+    auto other_l = [&](int c) -> float {
+        return sp.n_splits > 0 ? mt.ws_lse[static_cast<size_t>(sp.ws_row0 + c * sp.stride) * n_q_heads + head0 + hd]
+                               : mt.lse_a[rh];
+    };
+    // folds the other part's partials at element x, then this part's (lb, o2); stores 4 elements
+    auto fold_and_store = [&](int x, float lb, const float4& o2) -> float {
+        PartialFold f;
+        for (int c = 0; c < n_other; ++c) fold_add(f, other_l(c), *reinterpret_cast<const float4*>(other_o(c) + x));
+        fold_add(f, lb, o2);
+        float4 r;
+        const float lse = fold_result(f, r);
+        store_out4<true>(mt.o_out, rh * kD + x, r.x, r.y, r.z, r.w);
+        return lse;
+    };
     if (kv_len <= 0 && mt.o_a != nullptr) {      // empty part, fused merge: the other part passes through
         if (row_ok) {
-            const MergeWeights w = merge_weights(mt.lse_a[rh], -INFINITY);
-            for (int x = h * 64; x < h * 64 + 64; x += 4) {
-                const float4 a = *reinterpret_cast<const float4*>(mt.o_a + rh * kD + x);
-                store_out4<true>(mt.o_out, rh * kD + x, merge_value(w, a.x, 0.f), merge_value(w, a.y, 0.f),
-                                 merge_value(w, a.z, 0.f), merge_value(w, a.w, 0.f));
-            }
-            if (h == 0 && mt.lse_out != nullptr) mt.lse_out[rh] = w.lse;
+            float lse = -INFINITY;
+            for (int x = h * 64; x < h * 64 + 64; x += 4) lse = fold_and_store(x, -INFINITY, make_float4(0.f, 0.f, 0.f, 0.f));
+            if (h == 0 && mt.lse_out != nullptr) mt.lse_out[rh] = lse;
         }
         return;
     }
@@ -360,20 +379,51 @@ __global__ __launch_bounds__(64 * NW, 2) void tile_attention_kernel(
     // ---- epilogue: normalise and store O (transposed back), log-sum-exp --------------------------
     const float ltot = l_run + __shfl_xor(l_run, 32);
     if (row_ok && mt.o_a != nullptr) {
-        // fused merge: this part is (O / l, log-sum-exp), the other part's row comes from memory
-        const float inv = 1.f / ltot;
-        const MergeWeights w = merge_weights(mt.lse_a[rh], (m_run + log2f(ltot)) * kLn2);
+        // Fused merge: this part is (O / l, log-sum-exp lb), the other part comes from memory.  The
+        // weights of all parts (relative to their common maximum) come first, then every partial
+        // is added with its 16 row pieces fetched at once.
+        const float lb = (m_run + log2f(ltot)) * kLn2;          // finite: at least one key is visible
+        float top = lb;
+        for (int c = 0; c < n_other; ++c) top = fmaxf(top, other_l(c));
+        const float w_own = expf(lb - top);
+        float den = w_own;
+        for (int c = 0; c < n_other; ++c) {
+            const float lc = other_l(c);
+            if (lc != -INFINITY) den += expf(lc - top);
+        }
+        const float inv_den = 1.f / den;
+        const float s_own = w_own * inv_den / ltot;
 #pragma unroll
         for (int db = 0; db < 4; ++db)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const size_t off = rh * kD + 32 * db + 8 * i + 4 * h;
-                const float4 a = *reinterpret_cast<const float4*>(mt.o_a + off);
-                store_out4<true>(mt.o_out, off, merge_value(w, a.x, oacc[db][4 * i] * inv),
-                                 merge_value(w, a.y, oacc[db][4 * i + 1] * inv), merge_value(w, a.z, oacc[db][4 * i + 2] * inv),
-                                 merge_value(w, a.w, oacc[db][4 * i + 3] * inv));
-            }
-        if (h == 0 && mt.lse_out != nullptr) mt.lse_out[rh] = w.lse;
+            for (int x = 0; x < 16; ++x) oacc[db][x] *= s_own;
+        for (int c = 0; c < n_other; ++c) {
+            const float lc = other_l(c);
+            if (lc == -INFINITY) continue;                       // an empty partial's rows are never touched
+            const float wc = expf(lc - top) * inv_den;
+            const float* src = other_o(c);
+            float4 xs[16];
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) xs[4 * db + i] = *reinterpret_cast<const float4*>(src + 32 * db + 8 * i + 4 * h);
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    oacc[db][4 * i] = fmaf(wc, xs[4 * db + i].x, oacc[db][4 * i]);
+                    oacc[db][4 * i + 1] = fmaf(wc, xs[4 * db + i].y, oacc[db][4 * i + 1]);
+                    oacc[db][4 * i + 2] = fmaf(wc, xs[4 * db + i].z, oacc[db][4 * i + 2]);
+                    oacc[db][4 * i + 3] = fmaf(wc, xs[4 * db + i].w, oacc[db][4 * i + 3]);
+                }
+        }
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                store_out4<true>(mt.o_out, rh * kD + 32 * db + 8 * i + 4 * h, oacc[db][4 * i], oacc[db][4 * i + 1],
+                                 oacc[db][4 * i + 2], oacc[db][4 * i + 3]);
+        if (h == 0 && mt.lse_out != nullptr) mt.lse_out[rh] = top + logf(den);
     } else if (row_ok) {
         const float inv = 1.f / ltot;
         float* orow = dst_o + (static_cast<size_t>(tok) * n_q_heads + hd) * kD;

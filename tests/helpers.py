@@ -39,6 +39,11 @@ def run_hip_path(batch, vals, scale=0.0, want_lse=True, pg=None):
     o_f = torch.full_like(o, nan)
     lse_f = torch.full_like(l1, nan) if want_lse else None
     bllm.suffix_attention_merged(pg, q, ks, vs, o1, l1, o_f, lse_f)
+    # and through the one-call entry point (its workspace filled with NaN first)
+    o_c = torch.full_like(o, nan)
+    lse_c = torch.full_like(l1, nan) if want_lse else None
+    ws = torch.full((bllm.prefix_shared_workspace_bytes(pg) // 4 + 1,), nan, device=dev, dtype=torch.float32)
+    bllm.prefix_shared_attention(pg, q, kp, vp, ks, vs, ws, o_c, lse_c)
     torch.cuda.synchronize()
     inv = np.empty(T, dtype=np.int64)
     inv[meta["row_src"]] = np.arange(T)
@@ -46,9 +51,11 @@ def run_hip_path(batch, vals, scale=0.0, want_lse=True, pg=None):
     out = {"o": back(o), "o_prefix": back(o1), "lse_prefix": back(l1), "o_suffix": back(o2), "lse_suffix": back(l2),
            "meta": meta}
     out["o_fused"] = back(o_f)
+    out["o_one_call"] = back(o_c)
     if want_lse:
         out["lse"] = back(lse)
         out["lse_fused"] = back(lse_f)
+        out["lse_one_call"] = back(lse_c)
     if own:
         pg.destroy()
     return out

@@ -18,6 +18,9 @@ def check_all(batch, vals, scale=0.0, rows=None, requests=None):
     # the two-call sequence (suffix pass with the reduction in its epilogue) against the same oracle values
     errs["o_fused"] = max_abs_err(got["o_fused"], ref["o"], rows)
     errs["lse_fused"] = max_abs_err(got["lse_fused"], ref["lse"], rows)
+    # the one-call entry point (split prefixes folded piece by piece in the suffix kernels)
+    errs["o_one_call"] = max_abs_err(got["o_one_call"], ref["o"], rows)
+    errs["lse_one_call"] = max_abs_err(got["lse_one_call"], ref["lse"], rows)
     print(batch.name, "T=%d" % batch.n_rows, {k: "%.2e" % v for k, v in errs.items()}, flush=True)
     # fp32 path: everything within 1e-5.  bf16 path: the merged output (rounded to bf16)
     # within 2e-2; the fp32 partial outputs within 1e-2 (the matrix-core P.V product rounds the
@@ -25,7 +28,7 @@ def check_all(batch, vals, scale=0.0, rows=None, requests=None):
     # log-sum-exp comes from fp32 scores of exact bf16 products and stays within 1e-4.
     bf16 = batch.layer.dtype == workload.BF16
     for k, v in errs.items():
-        bound = tol if k in ("o", "o_fused") else (1e-4 if k.startswith("lse") else 1e-2) if bf16 else tol
+        bound = tol if k in ("o", "o_fused", "o_one_call") else (1e-4 if k.startswith("lse") else 1e-2) if bf16 else tol
         assert v <= bound, (k, v, bound)
     return got, ref
 
@@ -117,6 +120,8 @@ def test_empty_batch_is_a_no_op():
     bllm.suffix_attention(pg, None, None, None, None, None)
     bllm.lse_merge(pg, None, None, None, None, None)
     bllm.suffix_attention_merged(pg, None, None, None, None, None, None)
+    assert bllm.prefix_shared_workspace_bytes(pg) == 0
+    bllm.prefix_shared_attention(pg, None, None, None, None, None, None, None)
     pg.destroy()
 
 
@@ -149,6 +154,39 @@ def test_fused_suffix_pass_drops_rows_of_an_empty_prefix_part():
     pg.destroy()
 
 
+@pytest.mark.parametrize("suffixes", [[300, 5, 260, 17], [9, 5, 30, 17]])
+def test_many_prefix_splits_folded_in_the_suffix_epilogue(suffixes):
+    """One group with a long ragged prefix and few rows: the prefix is split eight ways, more
+    pieces than the suffix kernels request ahead, for decode rows (both wavefront-per-item
+    settings) and for prefill chunks."""
+    L = workload.Layer(8, 2, 128, workload.BF16)
+    s_len = np.array(suffixes + [90, 70], np.int32)
+    q_len = np.array([1] * len(suffixes) + [40, 70], np.int32)
+    b = workload.Batch("manysplits", L, np.array([4100], np.int32), np.zeros(len(s_len), np.int32), s_len, q_len)
+    got, _ = check_all(b, workload.draw_values(b, seed=5))
+    assert got["meta"]["prefix_split_len"] == 512 and got["meta"]["n_prefix_ws_rows"] == 9 * b.n_rows
+
+
+def test_one_call_rejects_a_small_or_misaligned_workspace():
+    import torch
+    import paper_2412_03594_amd as bllm
+    pg = bllm.prefix_group_create((8, 2, 128, workload.BF16, 0.0), [5], [0], [3], [1])
+    need = bllm.prefix_shared_workspace_bytes(pg)
+    assert need >= 8 * 129 * 4
+    dev = torch.device("cuda:0")
+    t = lambda *shape, dt=torch.bfloat16: torch.zeros(shape, device=dev, dtype=dt)
+    q, kp, ks, o = t(1, 8, 128), t(5, 2, 128), t(3, 2, 128), t(1, 8, 128)
+    small = torch.zeros(need // 4 - 1, device=dev, dtype=torch.float32)
+    with pytest.raises(bllm.BllmError):
+        bllm.prefix_shared_attention(pg, q, kp, kp, ks, ks, small, o)
+    big = torch.zeros(need // 4 + 8, device=dev, dtype=torch.float32)
+    with pytest.raises(bllm.BllmError):
+        bllm.prefix_shared_attention(pg, q, kp, kp, ks, ks, big[1:], o)      # 4-byte aligned only
+    bllm.prefix_shared_attention(pg, q, kp, kp, ks, ks, big, o)
+    torch.cuda.synchronize()
+    pg.destroy()
+
+
 def test_graph_replays_match_eager_launches():
     """The device calls of a step captured in a HIP graph: every replay, with eager work and
     synchronisation in between and with new contents in the same input tensors, gives bit for
@@ -171,8 +209,12 @@ def test_graph_replays_match_eager_launches():
     mk = lambda *shape, dt=torch.float32: torch.zeros(shape, device=dev, dtype=dt)
     bufs = {"o1": mk(T, 8, 128), "l1": mk(T, 8), "o2": mk(T, 8, 128), "l2": mk(T, 8),
             "o": mk(T, 8, 128, dt=torch.bfloat16), "lse": mk(T, 8)}
-    for fused in (False, True):
-        run = lambda: bllm.prefix_shared_attention(pg, cur[0], cur[1], cur[2], cur[3], cur[4], bufs, fused=fused)
+    ws = torch.zeros(bllm.prefix_shared_workspace_bytes(pg) // 4 + 1, device=dev, dtype=torch.float32)
+    for fused in (False, True, "one call"):
+        if fused == "one call":
+            run = lambda: bllm.prefix_shared_attention(pg, cur[0], cur[1], cur[2], cur[3], cur[4], ws, bufs["o"], bufs["lse"])
+        else:
+            run = lambda: bllm.three_call_attention(pg, cur[0], cur[1], cur[2], cur[3], cur[4], bufs, fused=fused)
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(side):
