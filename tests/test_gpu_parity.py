@@ -92,6 +92,38 @@ def test_l8b_mixed_sampled():
     check_all(b, v, rows=rows, requests=reqs)
 
 
+def test_zipf_group_sizes_rho8_sampled():
+    """The 70B-shaped recipe (64 query / 8 KV heads, Zipf group sizes, decode rows and chunks of
+    up to 512 rows, a token budget that leaves requests idle), scaled down so the inputs can be
+    drawn on the host in seconds; the oracle evaluates a sample of requests of every class."""
+    b = workload.l70b_zipf(0, token_budget=6000, n_groups=6, size_max=40, prefix_range=(256, 2500),
+                           suffix_range=(32, 400))
+    v = workload.draw_values(b)
+    rng = np.random.default_rng(4)
+    act_chunk = np.where(b.req_q_len > 1)[0]
+    act_dec = np.where(b.req_q_len == 1)[0]
+    reqs = np.concatenate([rng.choice(act_chunk, min(4, len(act_chunk)), replace=False),
+                           rng.choice(act_dec, min(16, len(act_dec)), replace=False)])
+    row0 = np.concatenate([[0], np.cumsum(b.req_q_len)])
+    rows = np.concatenate([np.arange(row0[r], row0[r + 1]) for r in reqs])
+    check_all(b, v, rows=rows, requests=reqs)
+
+
+def test_paper_shaped_batches():
+    """Shapes of the paper's own workloads: the kernel-benchmark setting prefix / distinct / all
+    requests in one group with decode rows and a few prefill requests (Sec. 4.3.3), and an
+    industry-shaped batch with share degree about 3 (Sec. 4.2.2), where the prefix pass has only
+    a dozen stacked rows per group."""
+    b = workload.kernel_bench_shape(2048, 256, 32, n_prefill=7)
+    v = workload.draw_values(b)
+    reqs = np.array([0, 5, 17, 31, 32, 38])
+    row0 = np.concatenate([[0], np.cumsum(b.req_q_len)])
+    rows = np.concatenate([np.arange(row0[r], row0[r + 1]) for r in reqs])
+    check_all(b, v, rows=rows, requests=reqs)
+    b = workload.industry_shaped(n_groups=40, seed=1)
+    check_all(b, workload.draw_values(b))
+
+
 def test_shuffled_user_order_and_idle_requests():
     b = workload.l8b_mixed(3, shuffle=True)
     # shrink: keep it small by cutting prefixes (same structure, ragged lengths)

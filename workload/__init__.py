@@ -145,21 +145,23 @@ def rank_longprefix(seed=0, shuffle=False):
     return _finish("rank_longprefix", layer, prefix_len, req_group, s, q, seed, shuffle, rng)
 
 
-def l70b_zipf(seed=0, shuffle=False, token_budget=None):
+def l70b_zipf(seed=0, shuffle=False, token_budget=None, n_groups=32, size_max=512, prefix_range=(256, 8192),
+              suffix_range=(32, 1024)):
     """Llama-3-70B-shaped: 64/8 heads, 32 groups, Zipf(1.1) sizes in 1..512,
     prefix U[256,8192], suffix U[32,1024]; each request is a decode row with
     probability 1/2, else a prefill chunk of min(512, s) rows.  token_budget
     (e.g. 32768) keeps chunks in request order until the budget is used; later
-    prefill-class requests are idle."""
+    prefill-class requests are idle.  The range arguments scale the same recipe down
+    (same draw order) for cases an oracle can cover."""
     rng = _rng(seed)
     layer = Layer(64, 8, 128, BF16)
-    g = 32
-    prefix_len = _uniform(rng, 256, 8192, g)
-    sizes = _zipf_sizes(rng, g, 1.1, 512)
+    g = n_groups
+    prefix_len = _uniform(rng, prefix_range[0], prefix_range[1], g)
+    sizes = _zipf_sizes(rng, g, 1.1, size_max)
     req_group = np.repeat(np.arange(g), sizes)
     n = int(sizes.sum())
     is_decode = rng.integers(0, 2, size=n) == 0
-    s = _uniform(rng, 32, 1024, n)
+    s = _uniform(rng, suffix_range[0], suffix_range[1], n)
     q = np.where(is_decode, 1, np.minimum(512, s))
     name = "l70b_zipf"
     if token_budget is not None:
