@@ -26,9 +26,10 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 # HBM bytes per launch of each pass, from rocprofv3 FETCH_SIZE + WRITE_SIZE runs scaled by a plain
 # copy of known size (the summaries and commands are under profiles/<workload>_kernels.md).
 MEASURED_TRAFFIC_BYTES = {
-    "l8b_decode": {"suffix": 306.8e6, "prefix": 108.0e6, "merge": 10.8e6, "suffix_merged": 309.2e6},
-    "rank_longprefix": {"suffix": 331.8e6, "prefix": 228.6e6, "merge": 43.0e6, "suffix_merged": 340.3e6},
-    "l8b_mixed": {"suffix": 823.5e6, "prefix": 664.6e6, "merge": 709.4e6, "suffix_merged": 989.9e6},
+    "l8b_decode": {"suffix": 306.8e6, "prefix": 109.6e6, "merge": 10.8e6, "suffix_merged": 309.2e6, "one_call": 410.9e6},
+    "rank_longprefix": {"suffix": 331.8e6, "prefix": 231.8e6, "merge": 43.0e6, "suffix_merged": 340.4e6,
+                        "one_call": 537.8e6},
+    "l8b_mixed": {"suffix": 848.3e6, "prefix": 692.6e6, "merge": 709.4e6, "suffix_merged": 999.6e6, "one_call": 1692.2e6},
 }
 
 
@@ -56,7 +57,9 @@ def algorithmic_work(batch, meta):
     # suffix pass with the reduction in its epilogue: reads the prefix partial instead of writing its
     # own, and writes the final output
     suffix_merged = {"bytes": suffix["bytes"] + float(T * hq * d * e), "flops": suffix["flops"]}
-    return {"prefix": prefix, "suffix": suffix, "merge": merge, "suffix_merged": suffix_merged}
+    # the whole path in one call: the prefix partial is written once and read once
+    one_call = {"bytes": prefix["bytes"] + suffix_merged["bytes"], "flops": prefix["flops"] + suffix["flops"]}
+    return {"prefix": prefix, "suffix": suffix, "merge": merge, "suffix_merged": suffix_merged, "one_call": one_call}
 
 
 def time_loop(fn, steps, warmup, torch):
@@ -110,7 +113,7 @@ def oracle_baseline(batch, vals, budget_s=15.0):
                       (done_reqs, len(order), len(by_group), done_rows, dt)}
 
 
-def run_workload(name, steps, warmup, seed, rotate, torch, bllm, workload, with_values_host=True, schedule="one_call",
+def run_workload(name, steps, warmup, seed, rotate, torch, bllm, workload, with_values_host=True, schedule="fused",
                  use_graph=False):
     batch = workload.CONFIGS[name](seed)
     L = batch.layer
@@ -225,10 +228,11 @@ def run_workload(name, steps, warmup, seed, rotate, torch, bllm, workload, with_
     t_pass = {"prefix": time_loop(prefix_pass, steps, warmup, torch),
               "suffix": time_loop(suffix_pass, steps, warmup, torch),
               "merge": time_loop(merge_pass, steps, warmup, torch),
-              "suffix_merged": time_loop(suffix_merged_pass, steps, warmup, torch)}
+              "suffix_merged": time_loop(suffix_merged_pass, steps, warmup, torch),
+              "one_call": time_loop(step_one_call, steps, warmup, torch)}
     work = algorithmic_work(batch, meta)
     passes = {}
-    for k in ("prefix", "suffix", "merge", "suffix_merged"):
+    for k in ("prefix", "suffix", "merge", "suffix_merged", "one_call"):
         sec = t_pass[k] * 1e-3
         passes[k] = {"ms": round(t_pass[k], 5), "GB_s": round(work[k]["bytes"] / sec / 1e9, 1),
                      "TFLOP_s": round(work[k]["flops"] / sec / 1e12, 2),
@@ -273,10 +277,10 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--rotate", type=int, default=0,
                     help="copies of the KV tensors cycled through (0: enough to defeat the Infinity Cache, 2..16)")
-    ap.add_argument("--schedule", choices=["one_call", "fused", "three_call"], default="one_call",
-                    help="timed step: the one-call entry point (prefix kernels, then suffix kernels that fold the prefix "
-                         "result - split pieces included - in their epilogue); prefix pass + suffix pass with the "
-                         "reduction in its epilogue (two calls); or prefix, suffix and merge passes (three calls).  "
+    ap.add_argument("--schedule", choices=["fused", "one_call", "three_call"], default="fused",
+                    help="timed step: prefix pass + suffix pass with the reduction in its epilogue (two calls); the "
+                         "one-call entry point (prefix kernels, then suffix kernels that fold the prefix result - split "
+                         "pieces included - in their epilogue); or prefix, suffix and merge passes (three calls).  "
                          "All give the same final output")
     ap.add_argument("--graph", action="store_true",
                     help="replay one captured HIP graph per timed step instead of launching eagerly (measured slower "
