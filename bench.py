@@ -244,6 +244,44 @@ def run_workload(name, steps, warmup, seed, rotate, torch, bllm, workload, with_
     return res
 
 
+def host_steps(batch, bllm, with_oracle=True):
+    """Host-side integer steps, in wall-clock time (no roofline applies): the token-batch packing of
+    the bench workload, and the global prefix identification on the paper's grouping-ablation input
+    (Sec. 4.4.1, setting A: 50 groups x 64 subcategories x 2 prompts of 1000 tokens), with the Python
+    reference timed beside it on 5 of the 50 groups."""
+    L = batch.layer
+    best = float("inf")
+    for _ in range(5):
+        t0 = time.perf_counter()
+        pg = bllm.prefix_group_create((L.n_q_heads, L.n_kv_heads, L.head_dim, L.dtype), batch.prefix_len, batch.req_group,
+                                      batch.req_suffix_len, batch.req_q_len, host_only=True)
+        best = min(best, time.perf_counter() - t0)
+        pg.destroy()
+    rng = np.random.default_rng(0)
+    rows = []
+    for _ in range(50):
+        gp = rng.integers(0, 1 << 30, 490)
+        for _ in range(64):
+            sp = rng.integers(0, 1 << 30, 11)
+            rows += [np.concatenate([gp, sp, rng.integers(0, 1 << 30, 499)]) for _ in range(2)]
+    flat = np.concatenate(rows).astype(np.int32)
+    start = np.arange(len(rows) + 1, dtype=np.int64) * 1000
+    t0 = time.perf_counter()
+    _, prefix_len, logical, processed = bllm.identify_prefix_groups_flat(start, flat)
+    t_ident = time.perf_counter() - t0
+    out = {"packing_us": round(best * 1e6, 1),
+           "prefix_identification": {"input": "6400 prompts x 1000 tokens, 490-token group prefix + 11-token sub prefix",
+                                     "ms": round(t_ident * 1e3, 2), "groups": int(len(prefix_len)),
+                                     "saving_ratio_percent": round(100.0 * (1.0 - processed / logical), 1)}}
+    if with_oracle:
+        from oracle import prefix_groups as ref
+        sample = [r.tolist() for r in rows[:5 * 128]]
+        t0 = time.perf_counter()
+        ref.identify_prefix_groups(sample)
+        out["prefix_identification"]["oracle_ms_on_640_prompts"] = round((time.perf_counter() - t0) * 1e3, 1)
+    return out
+
+
 def roofline_of(res):
     """Roofline record of the pass that takes the most time."""
     t = res["t_pass"]
@@ -330,6 +368,7 @@ def main():
         "roofline": roofline_of(main_res),
         "passes": main_res["passes"],
     }
+    out["host_steps"] = host_steps(batch, bllm, with_oracle=not args.no_cpu_baseline)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = oracle_baseline(batch, main_res["vals"])
     others = {}

@@ -216,6 +216,28 @@ int bllm_prefix_shared_attention(const bllm_prefix_groups* pg, const void* q,
                                  void* workspace, size_t workspace_bytes,
                                  void* o_out, float* lse_out, void* hip_stream);
 
+/* Global prefix identification on the host (Sec. 3.2): builds the compact prefix
+ * tree of the prompts, enlarges the first-level prefixes with the fork-and-merge
+ * pass of Alg. 1 (fork a first-level node and merge it with one of its children when
+ * (leaves(child) - 1) * tokens(child) exceeds tokens(node)), and returns the
+ * prefix-sharing groups: every first-level prefix shared by at least two prompts is
+ * a group; all other prompts share one group with prefix length 0.  Groups are
+ * numbered by their smallest prompt index.  The outputs are what
+ * bllm_prefix_group_create takes (prefix_len, req_group; a request's distinct length
+ * is its prompt length minus its group's prefix length).
+ *   prompt_start     host [n_prompts+1]  offsets into tokens, prompt_start[0] = 0
+ *   tokens           host [prompt_start[n_prompts]]  token ids
+ *   req_group        host out [n_prompts]
+ *   group_prefix_len host out, capacity n_prompts; *n_groups entries are written
+ *   n_logical_tokens, n_processed_tokens  host out, may be NULL: prefill tokens
+ *                    without and with the sharing (Eq. 1: saving ratio =
+ *                    1 - processed / logical)
+ * No device is touched.  Errors: INVALID_ARG, OUT_OF_MEMORY, UNSUPPORTED (a tree
+ * deeper than 20000 levels). */
+int bllm_identify_prefix_groups(int32_t n_prompts, const int64_t* prompt_start, const int32_t* tokens,
+                                int32_t* req_group, int32_t* group_prefix_len, int32_t* n_groups,
+                                int64_t* n_logical_tokens, int64_t* n_processed_tokens);
+
 const char* bllm_last_error(void);
 const char* bllm_version(void);
 

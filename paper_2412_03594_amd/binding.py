@@ -15,7 +15,7 @@ _LIB = None
 EXPORTS = ["bllm_prefix_group_create", "bllm_prefix_group_create_host", "bllm_prefix_group_metadata",
            "bllm_prefix_group_destroy", "bllm_shared_prefix_attention", "bllm_suffix_attention", "bllm_lse_merge",
            "bllm_suffix_attention_merged", "bllm_prefix_shared_attention", "bllm_prefix_shared_workspace_bytes",
-           "bllm_last_error", "bllm_version"]
+           "bllm_identify_prefix_groups", "bllm_last_error", "bllm_version"]
 
 
 class BllmError(RuntimeError):
@@ -79,6 +79,9 @@ def load_library():
     lib.bllm_prefix_shared_workspace_bytes.restype = C.c_size_t
     for name in EXPORTS[:9]:
         getattr(lib, name).restype = C.c_int
+    lib.bllm_identify_prefix_groups.argtypes = [C.c_int32, C.POINTER(C.c_int64), _I32P, _I32P, _I32P,
+                                                C.POINTER(C.c_int32), C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
+    lib.bllm_identify_prefix_groups.restype = C.c_int
     lib.bllm_last_error.restype = C.c_char_p
     lib.bllm_version.restype = C.c_char_p
     _LIB = lib
@@ -207,6 +210,31 @@ def suffix_attention_merged(pg, q, k_suffix, v_suffix, o_prefix, lse_prefix, o_o
 def lse_merge(pg, o_a, lse_a, o_b, lse_b, o_out, lse_out=None, stream=None):
     _check(load_library().bllm_lse_merge(pg.handle, _ptr(o_a), _ptr(lse_a), _ptr(o_b), _ptr(lse_b), _ptr(o_out),
                                          _ptr(lse_out), _stream(stream)))
+
+
+def identify_prefix_groups_flat(prompt_start, tokens):
+    """prompt_start: int64 [n+1] offsets into tokens (int32).  Returns (req_group, group_prefix_len,
+    n_logical_tokens, n_processed_tokens) from the library's host-side prefix identification."""
+    start = np.ascontiguousarray(prompt_start, dtype=np.int64)
+    flat = np.ascontiguousarray(tokens, dtype=np.int32)
+    n = len(start) - 1
+    req_group = np.zeros(max(n, 1), dtype=np.int32)
+    prefix_len = np.zeros(max(n, 1), dtype=np.int32)
+    n_groups = C.c_int32(0)
+    logical, processed = C.c_int64(0), C.c_int64(0)
+    _check(load_library().bllm_identify_prefix_groups(
+        n, start.ctypes.data_as(C.POINTER(C.c_int64)), flat.ctypes.data_as(_I32P), req_group.ctypes.data_as(_I32P),
+        prefix_len.ctypes.data_as(_I32P), C.byref(n_groups), C.byref(logical), C.byref(processed)))
+    return req_group[:n].copy(), prefix_len[:n_groups.value].copy(), int(logical.value), int(processed.value)
+
+
+def identify_prefix_groups(prompts):
+    """prompts: list of token-id sequences; see identify_prefix_groups_flat."""
+    start = np.zeros(len(prompts) + 1, dtype=np.int64)
+    np.cumsum([len(p) for p in prompts], out=start[1:])
+    flat = (np.concatenate([np.asarray(p, dtype=np.int32) for p in prompts]) if len(prompts) and start[-1]
+            else np.zeros(0, dtype=np.int32))
+    return identify_prefix_groups_flat(start, flat)
 
 
 def prefix_shared_workspace_bytes(pg):

@@ -1,0 +1,113 @@
+"""The library's host-side prefix identification (bllm_identify_prefix_groups, C ABI) against the
+reference in oracle/prefix_groups.py: bit for bit on hand-worked trees, random prompt sets and
+the paper-shaped workloads; then end to end into bllm_prefix_group_create's host packing."""
+import json
+import os
+
+import numpy as np
+import pytest
+
+import paper_2412_03594_amd as bllm
+from oracle import prefix_groups as ref
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+HAND = json.load(open(os.path.join(HERE, "golden", "prefix_groups_hand.json")))["cases"]
+
+
+def same(prompts):
+    want = ref.identify_prefix_groups(prompts)
+    req_group, prefix_len, logical, processed = bllm.identify_prefix_groups(prompts)
+    assert req_group.tolist() == want["req_group"]
+    assert prefix_len.tolist() == want["group_prefix_len"]
+    assert logical == want["n_logical_tokens"] and processed == want["n_processed_tokens"]
+    return want
+
+
+@pytest.mark.parametrize("name", sorted(HAND))
+def test_hand_worked_trees(name):
+    c = HAND[name]
+    req_group, prefix_len, logical, processed = bllm.identify_prefix_groups(c["prompts"])
+    assert req_group.tolist() == c["req_group"] and prefix_len.tolist() == c["group_prefix_len"]
+    assert (logical, processed) == (c["n_logical_tokens"], c["n_processed_tokens"])
+
+
+@pytest.mark.parametrize("seed", range(60))
+def test_random_prompt_sets(seed):
+    rng = np.random.default_rng(seed)
+    n = int(rng.integers(0, 40))
+    alphabet = int(rng.integers(2, 5))
+    max_len = int(rng.integers(1, 30))
+    prompts = [rng.integers(0, alphabet, int(rng.integers(0, max_len + 1))).tolist() for _ in range(n)]
+    if n > 3:                                   # duplicates and prompts that are prefixes of others
+        prompts[1] = list(prompts[0])
+        prompts[2] = prompts[0][: len(prompts[0]) // 2]
+    same(prompts)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_nested_templates(seed):
+    """Multi-level sharing as in retrieval prompts: template + document + question."""
+    rng = np.random.default_rng(100 + seed)
+    prompts = []
+    for _ in range(int(rng.integers(2, 5))):
+        template = rng.integers(0, 1000, int(rng.integers(1, 60))).tolist()
+        for _ in range(int(rng.integers(1, 6))):
+            doc = rng.integers(0, 1000, int(rng.integers(1, 200))).tolist()
+            for _ in range(int(rng.integers(1, 5))):
+                prompts.append(template + doc + rng.integers(0, 1000, int(rng.integers(0, 20))).tolist())
+    order = rng.permutation(len(prompts))
+    same([prompts[i] for i in order])
+
+
+def test_grouping_ablation_shape_and_micro_benchmark_shape():
+    rng = np.random.default_rng(3)
+    prompts = []
+    for _ in range(2):
+        gp = rng.integers(0, 1 << 30, 490).tolist()
+        for _ in range(64):
+            sp = rng.integers(0, 1 << 30, 11).tolist()
+            for _ in range(2):
+                prompts.append(gp + sp + rng.integers(0, 1 << 30, 499).tolist())
+    want = same(prompts)
+    assert want["group_prefix_len"] == [490, 490] and round(100 * want["saving_ratio"], 1) == 48.6
+    prompts = []
+    for _ in range(3):
+        pre = rng.integers(0, 1 << 30, 2000).tolist()
+        prompts += [pre + rng.integers(0, 1 << 30, 200).tolist() for _ in range(16)]
+    want = same(prompts)
+    assert round(100 * want["saving_ratio"], 1) == 85.2
+
+
+def test_groups_feed_the_packing():
+    """prompts -> groups -> bllm_prefix_group_create (host-only handle): the distinct part of every
+    request is its prompt minus its group's prefix; one decode step after a full prefill."""
+    rng = np.random.default_rng(5)
+    prompts = []
+    for _ in range(3):
+        pre = rng.integers(0, 100, 50).tolist()
+        prompts += [pre + rng.integers(100, 200, int(rng.integers(1, 9))).tolist() for _ in range(4)]
+    prompts.append(rng.integers(200, 300, 7).tolist())          # shares nothing
+    req_group, prefix_len, logical, processed = bllm.identify_prefix_groups(prompts)
+    assert prefix_len.tolist() == [50, 50, 50, 0]
+    distinct = np.array([len(p) for p in prompts]) - prefix_len[req_group]
+    pg = bllm.prefix_group_create((8, 2, 128, bllm.BF16), prefix_len, req_group, distinct + 1, np.ones(len(prompts), np.int32),
+                                  host_only=True)
+    meta = pg.metadata()
+    assert meta["n_rows"] == len(prompts) and meta["prefix_kv_start"].tolist() == [0, 50, 100, 150, 150]
+    pg.destroy()
+
+
+def test_invalid_arguments_and_empty_input():
+    import ctypes as C
+    lib = bllm.load_library()
+    n_groups = C.c_int32(-1)
+    start = (C.c_int64 * 1)(0)
+    assert lib.bllm_identify_prefix_groups(0, start, None, None, None, C.byref(n_groups), None, None) == 0
+    assert n_groups.value == 0
+    assert lib.bllm_identify_prefix_groups(-1, start, None, None, None, C.byref(n_groups), None, None) == -1
+    assert lib.bllm_identify_prefix_groups(0, None, None, None, None, C.byref(n_groups), None, None) == -1
+    bad = (C.c_int64 * 2)(0, -3)
+    rg, pl = (C.c_int32 * 1)(), (C.c_int32 * 1)()
+    assert lib.bllm_identify_prefix_groups(1, bad, None, rg, pl, C.byref(n_groups), None, None) == -1
+    req_group, prefix_len, logical, processed = bllm.identify_prefix_groups([[], []])   # two empty prompts
+    assert req_group.tolist() == [0, 0] and prefix_len.tolist() == [0] and logical == 0
