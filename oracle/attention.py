@@ -18,10 +18,15 @@ Readings taken where the paper is silent (the paper never prints the formula):
     already part of the suffix KV); row i sees suffix positions 0 .. s-q+i;
   * grouped-query attention maps query head h to KV head h // (Hq // Hkv);
   * the log-sum-exp is the natural log of sum exp(scale * q.k);
-  * an empty part has output 0 and log-sum-exp -inf.
+  * an empty part has output 0 and log-sum-exp -inf;
+  * tokens of a common prefix that are prefilled in this iteration (the common-prefix
+    queue of Sec. 3.3.1 feeds the same token batch) are the last prefix_q_len[g]
+    positions of the group's prefix KV so far; such a row sees the prefix positions up
+    to its own (plain causal attention), and has no suffix part.
 
 Row order here is the USER row order: requests in the order given, the q rows of
-a request consecutive.  Mapping to the library's packed order is the tests' job.
+a request consecutive; then the prefix rows, group by group.  Mapping to the
+library's packed order is the tests' job.
 """
 import numpy as np
 
@@ -85,13 +90,17 @@ def lse_merge(o_a, lse_a, o_b, lse_b):
 def prefix_shared_attention(q, k_prefix, v_prefix, k_suffix, v_suffix,
                             prefix_len, req_group, req_suffix_len, req_q_len,
                             n_q_heads, n_kv_heads, scale=None, requests=None,
-                            parts=True):
+                            parts=True, prefix_q_len=None, prefix_groups=None):
     """Attention of a token batch whose requests share per-group prefix KV.
 
     q                  [T, Hq, D]      user row order, T = sum(req_q_len)
     k_prefix, v_prefix [sum Lp, Hkv, D] group g at rows sum(prefix_len[:g]) ...
     k_suffix, v_suffix [sum s, Hkv, D]  request r at rows sum(req_suffix_len[:r]) ...
+    prefix_q_len: optional [G]; group g also has prefix_q_len[g] query rows at prefix
+           positions Lp_g - prefix_q_len[g] .. Lp_g - 1 (rows after all request rows).
     requests: optional iterable of request indices to evaluate (others stay NaN).
+    prefix_groups: optional iterable of groups whose prefix rows to evaluate (default:
+           all when requests is None, none otherwise).
     parts: also evaluate the formula on the prefix keys alone and the suffix keys
            alone (False leaves those four arrays NaN).
 
@@ -111,7 +120,9 @@ def prefix_shared_attention(q, k_prefix, v_prefix, k_suffix, v_suffix,
     req_q_len = np.asarray(req_q_len, dtype=np.int64)
     t_rows, hq, d = q.shape
     assert hq == n_q_heads and n_q_heads % n_kv_heads == 0
-    assert t_rows == int(req_q_len.sum())
+    prefix_q_len = (np.zeros(len(prefix_len), dtype=np.int64) if prefix_q_len is None
+                    else np.asarray(prefix_q_len, dtype=np.int64))
+    assert t_rows == int(req_q_len.sum()) + int(prefix_q_len.sum())
     rho = n_q_heads // n_kv_heads
     if scale is None:
         scale = 1.0 / np.sqrt(d)
@@ -159,4 +170,30 @@ def prefix_shared_attention(q, k_prefix, v_prefix, k_suffix, v_suffix,
             o, l = attend_one(qr, ks, vs, scale, vis_suffix)
             out["o_suffix"][r0:r0 + nq, h] = o
             out["lse_suffix"][r0:r0 + nq, h] = l
+
+    # rows of prefixes that are being prefilled: causal attention inside the prefix
+    prow_start = int(req_q_len.sum()) + np.concatenate([[0], np.cumsum(prefix_q_len)])
+    if prefix_groups is None:
+        prefix_groups = range(len(prefix_len)) if requests is None else []
+    for g in prefix_groups:
+        g = int(g)
+        nq = int(prefix_q_len[g])
+        if nq == 0:
+            continue
+        lp = int(prefix_len[g])
+        assert lp >= nq
+        r0 = int(prow_start[g])
+        vis_prefix = lp - nq + np.arange(nq) + 1
+        for h in range(n_q_heads):
+            kv_head = h // rho
+            k_own = k_prefix[pre_start[g]:pre_start[g] + lp, kv_head, :]
+            v_own = v_prefix[pre_start[g]:pre_start[g] + lp, kv_head, :]
+            o, l = attend_one(q[r0:r0 + nq, h, :], k_own, v_own, scale, vis_prefix)
+            out["o"][r0:r0 + nq, h] = o
+            out["lse"][r0:r0 + nq, h] = l
+            if parts:
+                out["o_prefix"][r0:r0 + nq, h] = o
+                out["lse_prefix"][r0:r0 + nq, h] = l
+                out["o_suffix"][r0:r0 + nq, h] = 0.0
+                out["lse_suffix"][r0:r0 + nq, h] = -np.inf
     return out

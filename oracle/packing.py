@@ -11,7 +11,15 @@ code so the two can be compared bit for bit:
         (group, 0 if q_len == 1 else 1, user index);
   * the rows of a request are consecutive, in suffix-position order;
   * row i of a request with suffix length s and q rows sits at suffix
-    position s - q + i.
+    position s - q + i;
+  * the rows of prefixes that are being prefilled in this iteration (the last
+    prefix_q_len[g] positions of group g's prefix) come after all request rows,
+    group by group, in position order, in the user's row order and in the packed
+    order alike; they belong to no request (row_req = -1) and row_pos is their
+    prefix position;
+  * row_kv_dst says where the new K/V of a packed row belongs: d >= 0 is row d of
+    the suffix KV arrays (req_kv_start[request] + row_pos), d < 0 is row -d - 1 of
+    the prefix KV arrays (prefix_kv_start[group] + row_pos).
 
 build_work_lists re-derives, by the documented rules, the work lists the kernels
 consume (tile items, streaming items, split tables).  All arrays are int32.
@@ -19,8 +27,12 @@ consume (tile items, streaming items, split tables).  All arrays are int32.
 import numpy as np
 
 
-def pack_token_batch(prefix_len, req_group, req_suffix_len, req_q_len):
+def pack_token_batch(prefix_len, req_group, req_suffix_len, req_q_len, prefix_q_len=None):
     prefix_len = [int(x) for x in prefix_len]
+    prefix_q_len = [0] * len(prefix_len) if prefix_q_len is None else [int(x) for x in prefix_q_len]
+    assert len(prefix_q_len) == len(prefix_len)
+    for g in range(len(prefix_len)):
+        assert 0 <= prefix_q_len[g] <= prefix_len[g]
     req_group = [int(x) for x in req_group]
     req_suffix_len = [int(x) for x in req_suffix_len]
     req_q_len = [int(x) for x in req_q_len]
@@ -65,6 +77,17 @@ def pack_token_batch(prefix_len, req_group, req_suffix_len, req_q_len):
         group_row_start[g + 1] = group_row_start[g] + rows
         group_decode_rows[g] = sum(1 for a in members if req_q_len[perm_req[a]] == 1)
 
+    # prefix rows: after the request rows (same place in the user's order: identity row_src)
+    row_kv_dst = [req_kv_start[r] + pos for r, pos in zip(row_req, row_pos)]
+    group_prefix_row_start = [len(row_req)]
+    for g in range(n_groups):
+        for i in range(prefix_q_len[g]):
+            row_src.append(len(row_req))
+            row_req.append(-1)
+            row_pos.append(prefix_len[g] - prefix_q_len[g] + i)
+            row_kv_dst.append(-(prefix_kv_start[g] + row_pos[-1]) - 1)
+        group_prefix_row_start.append(len(row_req))
+
     i32 = lambda x: np.asarray(x, dtype=np.int32)
     return {
         "n_rows": len(row_req),
@@ -74,11 +97,13 @@ def pack_token_batch(prefix_len, req_group, req_suffix_len, req_q_len):
         "group_req_start": i32(group_req_start),
         "group_row_start": i32(group_row_start),
         "group_decode_rows": i32(group_decode_rows),
+        "group_prefix_row_start": i32(group_prefix_row_start),
         "prefix_kv_start": i32(prefix_kv_start),
         "req_kv_start": i32(req_kv_start),
         "row_req": i32(row_req),
         "row_pos": i32(row_pos),
         "row_src": i32(row_src),
+        "row_kv_dst": i32(row_kv_dst),
     }
 
 
@@ -114,6 +139,7 @@ def build_work_lists(meta, prefix_len, req_suffix_len, req_q_len, n_q_heads, n_k
     rks = [int(x) for x in meta["req_kv_start"]]
     rrs = [int(x) for x in meta["req_row_start"]]
     perm = [int(x) for x in meta["perm_req"]]
+    gprs = [int(x) for x in meta["group_prefix_row_start"]]
     row_req = [int(x) for x in meta["row_req"]]
     row_pos = [int(x) for x in meta["row_pos"]]
     mfma = bool(is_bf16) and head_dim == 128
@@ -129,6 +155,7 @@ def build_work_lists(meta, prefix_len, req_suffix_len, req_q_len, n_q_heads, n_k
         base_items, max_lp = 0, 0
         for g in range(G):
             rows = grs[g + 1] - grs[g]
+            base_items += _ceil_div(gprs[g + 1] - gprs[g], br) * n_kv_heads
             if rows == 0 or prefix_len[g] == 0:
                 continue
             base_items += _ceil_div(rows, br) * n_kv_heads
@@ -140,6 +167,13 @@ def build_work_lists(meta, prefix_len, req_suffix_len, req_q_len, n_q_heads, n_k
             if ln < max_lp:
                 split_len = ln
         for g in range(G):
+            # prefix rows: causal inside the prefix, never split, written directly
+            n_pre = gprs[g + 1] - gprs[g]
+            for i0 in range(0, n_pre, br):
+                n = min(br, n_pre - i0)
+                first_vis = prefix_len[g] - n_pre + i0 + 1
+                for j in range(n_kv_heads):
+                    prefix_tiles.append([gprs[g] + i0, n, j, pks[g], first_vis + n - 1, first_vis, -1, 0])
             row0 = grs[g]
             rows = grs[g + 1] - row0
             if rows == 0:
@@ -173,9 +207,16 @@ def build_work_lists(meta, prefix_len, req_suffix_len, req_q_len, n_q_heads, n_k
             for t in range(grs[g], grs[g + 1]):
                 for j in range(n_kv_heads):
                     prefix_rows.append([t, 1, j, pks[g], prefix_len[g], prefix_len[g], -1, 0])
-        for t in range(T):
+            for t in range(gprs[g], gprs[g + 1]):
+                for j in range(n_kv_heads):
+                    prefix_rows.append([t, 1, j, pks[g], row_pos[t] + 1, row_pos[t] + 1, -1, 0])
+        for t in range(gprs[0]):
             for j in range(n_kv_heads):
                 suffix_rows.append([t, 1, j, rks[row_req[t]], row_pos[t] + 1, row_pos[t] + 1, -1, 0])
+    # prefix rows have no suffix part: empty streaming items write their 0 / -inf
+    for t in range(gprs[0], T):
+        for j in range(n_kv_heads):
+            suffix_rows.append([t, 1, j, 0, 0, 0, -1, 0])
     # prefix tile items: longest KV range first (stable); suffix tile items keep request order
     prefix_tiles.sort(key=lambda it: -it[4])
     # streaming items: longest range first (stable)

@@ -18,7 +18,7 @@ def run_oracle(batch, vals, **kw):
     return oa.prefix_shared_attention(
         vals["q"], vals["k_prefix"], vals["v_prefix"], vals["k_suffix"], vals["v_suffix"],
         batch.prefix_len, batch.req_group, batch.req_suffix_len, batch.req_q_len,
-        L.n_q_heads, L.n_kv_heads, **kw)
+        L.n_q_heads, L.n_kv_heads, prefix_q_len=batch.prefix_q_len, **kw)
 
 
 def brute_force(batch, vals, scale=None):
@@ -41,6 +41,7 @@ def brute_force(batch, vals, scale=None):
     c = 0
     for g, lp in enumerate(batch.prefix_len):
         key_group[c:c + lp] = g
+        key_pos[c:c + lp] = np.arange(lp)
         c += lp
     for r, s in enumerate(batch.req_suffix_len):
         key_req[c:c + s] = r
@@ -51,7 +52,15 @@ def brute_force(batch, vals, scale=None):
     row_pos = np.concatenate([np.arange(s - n, s) for s, n in
                               zip(batch.req_suffix_len, batch.req_q_len)] + [np.zeros(0, int)])
     row_group = batch.req_group[row_req]
-    vis = (key_is_prefix[None, :] & (key_group[None, :] == row_group[:, None])) | \
+    row_in_prefix = np.zeros(row_req.shape[0], dtype=bool)
+    # rows of prefixes that are being prefilled come last: no request, a position inside the prefix
+    pq = batch.prefix_rows
+    row_req = np.concatenate([row_req, np.full(int(pq.sum()), -1)])
+    row_group = np.concatenate([row_group, np.repeat(np.arange(batch.n_groups), pq)])
+    row_pos = np.concatenate([row_pos] + [np.arange(lp - n, lp) for lp, n in zip(batch.prefix_len, pq)])
+    row_in_prefix = np.concatenate([row_in_prefix, np.ones(int(pq.sum()), dtype=bool)])
+    vis = (key_is_prefix[None, :] & (key_group[None, :] == row_group[:, None]) &
+           (~row_in_prefix[:, None] | (key_pos[None, :] <= row_pos[:, None]))) | \
           ((~key_is_prefix)[None, :] & (key_req[None, :] == row_req[:, None]) &
            (key_pos[None, :] <= row_pos[:, None]))
     if scale is None:
@@ -77,6 +86,68 @@ def test_brute_force_ragged(seed):
     o, lse, _ = brute_force(b, v)
     np.testing.assert_allclose(out["o"], o, rtol=0, atol=1e-12)
     np.testing.assert_allclose(out["lse"], lse, rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_brute_force_with_prefix_rows(seed):
+    """Token batches in which some prefixes are being prefilled: those rows see the prefix
+    causally and nothing else."""
+    b = workload.with_prefix_prefill(workload.ragged_toy(seed), seed=seed)
+    assert b.prefix_rows.sum() > 0
+    v = workload.draw_values(b)
+    out = run_oracle(b, v)
+    o, lse, vis = brute_force(b, v)
+    n_req_rows = b.n_request_rows
+    t = n_req_rows
+    for g, n in enumerate(b.prefix_rows):
+        lp = int(b.prefix_len[g])
+        assert vis[t:t + n].sum(1).tolist() == list(range(lp - n + 1, lp + 1))
+        t += n
+    np.testing.assert_allclose(out["o"], o, rtol=0, atol=1e-12)
+    np.testing.assert_allclose(out["lse"], lse, rtol=0, atol=1e-12)
+    # the parts of a prefix row: everything is the prefix part, the suffix part is empty
+    np.testing.assert_array_equal(out["o_prefix"][n_req_rows:], out["o"][n_req_rows:])
+    np.testing.assert_array_equal(out["lse_prefix"][n_req_rows:], out["lse"][n_req_rows:])
+    assert (out["o_suffix"][n_req_rows:] == 0).all() and np.isneginf(out["lse_suffix"][n_req_rows:]).all()
+    # the request rows do not change when prefix rows join the batch
+    plain = run_oracle(workload.ragged_toy(seed), dict(v, q=v["q"][:n_req_rows]))
+    np.testing.assert_array_equal(plain["o"], out["o"][:n_req_rows])
+
+
+def test_prefix_rows_are_plain_causal_attention():
+    """A prefix prefilled in one go is causal self-attention, a stock library routine; a later
+    chunk is the tail of the same result."""
+    torch = pytest.importorskip("torch")
+    L = workload.Layer(4, 2, 32, workload.F32)
+    lp = 23
+    for n in (lp, 7, 1):
+        b = workload.Batch("p", L, np.array([5, lp], np.int32), np.zeros(0, np.int32), np.zeros(0, np.int32),
+                           np.zeros(0, np.int32), prefix_q_len=np.array([0, n], np.int32))
+        v = workload.draw_values(b, seed=3)
+        out = run_oracle(b, v)
+        k = torch.from_numpy(v["k_prefix"][5:].astype(np.float64)).permute(1, 0, 2).repeat_interleave(2, 0)
+        vv = torch.from_numpy(v["v_prefix"][5:].astype(np.float64)).permute(1, 0, 2).repeat_interleave(2, 0)
+        qfull = torch.zeros(4, lp, 32, dtype=torch.float64)
+        qfull[:, lp - n:] = torch.from_numpy(v["q"].astype(np.float64)).permute(1, 0, 2)
+        ref = torch.nn.functional.scaled_dot_product_attention(qfull, k, vv, is_causal=True)
+        np.testing.assert_allclose(out["o"], ref[:, lp - n:].permute(1, 0, 2).numpy(), atol=1e-12)
+
+
+def test_prefix_row_equals_request_row_without_prefix():
+    """A prefix row at position p is the row of a request with an empty prefix whose own
+    context is that prefix."""
+    L = workload.Layer(4, 2, 16, workload.F32)
+    b = workload.Batch("p", L, np.array([19], np.int32), np.zeros(0, np.int32), np.zeros(0, np.int32),
+                       np.zeros(0, np.int32), prefix_q_len=np.array([6], np.int32))
+    v = workload.draw_values(b, seed=8)
+    a = run_oracle(b, v)
+    as_req = workload.Batch("r", L, np.array([0], np.int32), np.array([0], np.int32), np.array([19], np.int32),
+                            np.array([6], np.int32))
+    vr = dict(q=v["q"], k_prefix=v["k_prefix"][:0], v_prefix=v["v_prefix"][:0], k_suffix=v["k_prefix"],
+              v_suffix=v["v_prefix"])
+    c = run_oracle(as_req, vr)
+    np.testing.assert_array_equal(a["o"], c["o"])
+    np.testing.assert_array_equal(a["lse"], c["lse"])
 
 
 def test_brute_force_tiny_fp32_config():
@@ -409,6 +480,12 @@ MUTATIONS = [
      "o, l = attend_one(qr, k_all, v_all, scale, vis_suffix)"),                                # prefix not counted
     ("kp = k_prefix[pre_start[g]:pre_start[g] + lp, j, :]", "kp = k_prefix[0:lp, j, :]"),      # wrong group's prefix
     ("w_b = np.exp(lse_b - safe_top)", "w_b = np.exp(lse_a - safe_top)"),                      # merge weight
+    ("vis_prefix = lp - nq + np.arange(nq) + 1", "vis_prefix = lp - nq + np.arange(nq)"),      # prefix rows: off by one
+    ("vis_prefix = lp - nq + np.arange(nq) + 1", "vis_prefix = np.arange(nq) + 1"),            # prefix chunk at the start
+    ("vis_prefix = lp - nq + np.arange(nq) + 1", "vis_prefix = lp + 0 * np.arange(nq)"),       # prefix rows not causal
+    ("kv_head = h // rho", "kv_head = h % n_kv_heads"),                                        # GQA mapping, prefix rows
+    ("k_own = k_prefix[pre_start[g]:pre_start[g] + lp, kv_head, :]", "k_own = k_prefix[0:lp, kv_head, :]"),
+    ("r0 = int(prow_start[g])", "r0 = int(prow_start[0]) + g"),                                # wrong q rows
 ]
 
 
@@ -424,12 +501,17 @@ def test_pins_catch_planted_mistakes(idx):
     exec(compile(src.replace(old, new), "oracle_mutant", "exec"), mod.__dict__)
     caught = False
     for seed in range(4):
-        b = workload.ragged_toy(seed, n_q_heads=4, n_kv_heads=2)
+        b = workload.with_prefix_prefill(workload.ragged_toy(seed, n_q_heads=4, n_kv_heads=2), seed=seed)
         v = workload.draw_values(b)
         L = b.layer
-        out = mod.prefix_shared_attention(
-            v["q"], v["k_prefix"], v["v_prefix"], v["k_suffix"], v["v_suffix"], b.prefix_len,
-            b.req_group, b.req_suffix_len, b.req_q_len, L.n_q_heads, L.n_kv_heads)
+        try:
+            out = mod.prefix_shared_attention(
+                v["q"], v["k_prefix"], v["v_prefix"], v["k_suffix"], v["v_suffix"], b.prefix_len,
+                b.req_group, b.req_suffix_len, b.req_q_len, L.n_q_heads, L.n_kv_heads,
+                prefix_q_len=b.prefix_q_len)
+        except (ValueError, IndexError, AssertionError):
+            caught = True
+            continue
         o, lse, _ = brute_force(b, v)
         mo, ml = mod.lse_merge(out["o_prefix"], out["lse_prefix"], out["o_suffix"], out["lse_suffix"])
         bad = (not np.allclose(out["o"], o, atol=1e-9) or not np.allclose(out["lse"], lse, atol=1e-9)

@@ -39,6 +39,18 @@ class Batch:
     req_q_len: np.ndarray         # [R] int32  (0 idle, 1 decode, >1 prefill chunk)
     seed: int = 0
     note: str = ""
+    prefix_q_len: np.ndarray = None   # [G] int32 rows of each prefix prefilled this iteration (None: none)
+
+    @property
+    def prefix_rows(self):
+        """[G] prefix rows per group (zeros when no prefix is being prefilled)."""
+        if self.prefix_q_len is None:
+            return np.zeros(self.prefix_len.shape[0], dtype=np.int32)
+        return np.asarray(self.prefix_q_len, dtype=np.int32)
+
+    @property
+    def n_request_rows(self):
+        return int(self.req_q_len.sum())
 
     @property
     def n_groups(self):
@@ -50,7 +62,7 @@ class Batch:
 
     @property
     def n_rows(self):
-        return int(self.req_q_len.sum())
+        return int(self.req_q_len.sum()) + int(self.prefix_rows.sum())
 
     @property
     def n_prefix_kv(self):
@@ -229,6 +241,30 @@ def ragged_toy(seed=0, dtype=F32, n_q_heads=4, n_kv_heads=2, head_dim=64, shuffl
     if q.sum() == 0:
         q[0] = 1
     return _finish("ragged_toy", layer, prefix_len, req_group, s, q, seed, shuffle, rng)
+
+
+def with_prefix_prefill(batch, seed=0, max_rows=None):
+    """The same batch with some prefixes still being prefilled in this iteration (Sec. 3.3.1: the
+    common-prefix queue feeds the token batch too): a seeded draw gives every non-empty prefix
+    either no rows, a chunk of its last positions, or all its positions (first chunk = whole
+    prefix so far).  max_rows bounds a chunk."""
+    rng = _rng(seed, 7)
+    pq = np.zeros(batch.n_groups, dtype=np.int32)
+    for g, lp in enumerate(batch.prefix_len):
+        lp = int(lp)
+        if lp == 0:
+            continue
+        cls = int(rng.integers(0, 3))
+        cap = lp if max_rows is None else min(lp, max_rows)
+        if cls == 1:
+            pq[g] = int(rng.integers(1, cap + 1))
+        elif cls == 2:
+            pq[g] = cap
+    if pq.sum() == 0 and batch.prefix_len.max() > 0:
+        g = int(np.argmax(batch.prefix_len))
+        pq[g] = min(int(batch.prefix_len[g]), max_rows or int(batch.prefix_len[g]))
+    return Batch(batch.name + "+prefill", batch.layer, batch.prefix_len, batch.req_group, batch.req_suffix_len,
+                 batch.req_q_len, seed=batch.seed, note=batch.note, prefix_q_len=pq)
 
 
 CONFIGS = {
