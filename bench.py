@@ -39,13 +39,16 @@ def algorithmic_work(batch, meta):
     e = 2 if L.dtype == 1 else 4
     hq, hkv, d = L.n_q_heads, L.n_kv_heads, L.head_dim
     T = batch.n_rows
-    rows_g = np.diff(meta["group_row_start"]).astype(np.float64)
+    rows_g = np.diff(meta["group_row_start"]).astype(np.float64)      # request rows: they see the whole prefix
+    pre_g = np.diff(meta["group_prefix_row_start"]).astype(np.float64)  # prefix rows: causal inside the prefix
     lp = batch.prefix_len.astype(np.float64)
-    used = rows_g > 0
+    used = (rows_g + pre_g) > 0
     q_bytes = T * hq * d * e
     part_bytes = T * hq * (4 * d + 4)
+    # prefix row i of n sees lp - n + i + 1 keys
+    pre_vis = pre_g * (lp - pre_g) + pre_g * (pre_g + 1) / 2
     prefix = {"bytes": float(2 * (lp * used).sum() * hkv * d * e + q_bytes + part_bytes),
-              "flops": float(4 * (rows_g * lp).sum() * hq * d)}
+              "flops": float(4 * ((rows_g * lp).sum() + pre_vis.sum()) * hq * d)}
     act = batch.req_q_len > 0
     s = batch.req_suffix_len.astype(np.float64)
     nq = batch.req_q_len.astype(np.float64)
@@ -59,7 +62,10 @@ def algorithmic_work(batch, meta):
     suffix_merged = {"bytes": suffix["bytes"] + float(T * hq * d * e), "flops": suffix["flops"]}
     # the whole path in one call: the prefix partial is written once and read once
     one_call = {"bytes": prefix["bytes"] + suffix_merged["bytes"], "flops": prefix["flops"] + suffix["flops"]}
-    return {"prefix": prefix, "suffix": suffix, "merge": merge, "suffix_merged": suffix_merged, "one_call": one_call}
+    # the new K/V rows of the batch's own tokens: read once, written once, plus the destination index
+    kv_append = {"bytes": float(T * (2 * 2 * hkv * d * e + 4)), "flops": 0.0}
+    return {"prefix": prefix, "suffix": suffix, "merge": merge, "suffix_merged": suffix_merged, "one_call": one_call,
+            "kv_append": kv_append}
 
 
 def time_loop(fn, steps, warmup, torch):
@@ -120,7 +126,8 @@ def run_workload(name, steps, warmup, seed, rotate, torch, bllm, workload, with_
     dev = torch.device("cuda:0")
     tdt = torch.bfloat16 if L.dtype == workload.BF16 else torch.float32
     pg = bllm.prefix_group_create((L.n_q_heads, L.n_kv_heads, L.head_dim, L.dtype), batch.prefix_len,
-                                  batch.req_group, batch.req_suffix_len, batch.req_q_len)
+                                  batch.req_group, batch.req_suffix_len, batch.req_q_len,
+                                  prefix_q_len=batch.prefix_q_len)
     meta = pg.metadata()
     T = meta["n_rows"]
     vals = workload.draw_values(batch) if with_values_host else None
@@ -162,6 +169,21 @@ def run_workload(name, steps, warmup, seed, rotate, torch, bllm, workload, with_
     def suffix_pass():
         b = nxt()
         bllm.suffix_attention(pg, q, b[2], b[3], o2, l2)
+
+    # the batch's own K/V rows as they already are in copy 0: appending them again changes nothing
+    dst = torch.from_numpy(meta["row_kv_dst"].astype(np.int64)).to(dev)
+    to_prefix = dst < 0
+
+    def own_rows(pre, suf):
+        out = torch.empty((T, L.n_kv_heads, L.head_dim), device=dev, dtype=tdt)
+        out[~to_prefix] = suf[dst[~to_prefix]]
+        out[to_prefix] = pre[-dst[to_prefix] - 1]
+        return out
+    k_new, v_new = own_rows(kv[0][0], kv[0][2]), own_rows(kv[0][1], kv[0][3])
+
+    def kv_append_pass():
+        b = kv[0]
+        bllm.kv_append(pg, k_new, v_new, b[0], b[1], b[2], b[3])
 
     def merge_pass():
         bllm.lse_merge(pg, o1, l1, o2, l2, o, None)
@@ -229,10 +251,11 @@ def run_workload(name, steps, warmup, seed, rotate, torch, bllm, workload, with_
               "suffix": time_loop(suffix_pass, steps, warmup, torch),
               "merge": time_loop(merge_pass, steps, warmup, torch),
               "suffix_merged": time_loop(suffix_merged_pass, steps, warmup, torch),
-              "one_call": time_loop(step_one_call, steps, warmup, torch)}
+              "one_call": time_loop(step_one_call, steps, warmup, torch),
+              "kv_append": time_loop(kv_append_pass, steps, warmup, torch)}
     work = algorithmic_work(batch, meta)
     passes = {}
-    for k in ("prefix", "suffix", "merge", "suffix_merged", "one_call"):
+    for k in ("prefix", "suffix", "merge", "suffix_merged", "one_call", "kv_append"):
         sec = t_pass[k] * 1e-3
         passes[k] = {"ms": round(t_pass[k], 5), "GB_s": round(work[k]["bytes"] / sec / 1e9, 1),
                      "TFLOP_s": round(work[k]["flops"] / sec / 1e12, 2),
@@ -310,7 +333,7 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="l8b_decode")
-    ap.add_argument("--also", default="rank_longprefix,l8b_mixed",
+    ap.add_argument("--also", default="rank_longprefix,l8b_mixed,l8b_decode_prefill",
                     help="comma-separated extra workloads reported under 'other_workloads' ('' for none)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--rotate", type=int, default=0,

@@ -65,10 +65,13 @@ typedef struct bllm_prefix_groups bllm_prefix_groups;   /* opaque, immutable aft
 /* Host views of the packing metadata of a handle (valid until destroy).
  * Packed order: active requests (q_len > 0) stably sorted by
  * (group, decode row before prefill chunk, user index); rows of a request
- * consecutive in suffix-position order. */
+ * consecutive in suffix-position order.  Rows of prefixes that are prefilled
+ * in the same iteration (bllm_prefix_group_create_ex) come after all request
+ * rows, group by group, in position order, in the user's row order and in the
+ * packed order alike. */
 typedef struct {
     int32_t n_groups, n_requests;
-    int32_t n_rows;                    /* T = sum of q_len */
+    int32_t n_rows;                    /* T = sum of q_len + sum of prefix_q_len */
     int32_t n_active;                  /* requests with q_len > 0 */
     const int32_t* perm_req;           /* [n_active]   packed request -> user request */
     const int32_t* req_row_start;      /* [n_active+1] first packed row of each packed request */
@@ -77,9 +80,11 @@ typedef struct {
     const int32_t* group_decode_rows;  /* [G]   decode rows of the group (they come first) */
     const int32_t* prefix_kv_start;    /* [G+1] first prefix KV row of each group */
     const int32_t* req_kv_start;       /* [R+1] first suffix KV row of each USER request */
-    const int32_t* row_req;            /* [T]   user request of each packed row */
-    const int32_t* row_pos;            /* [T]   suffix position of each packed row */
+    const int32_t* row_req;            /* [T]   user request of each packed row; -1 for a prefix row */
+    const int32_t* row_pos;            /* [T]   suffix position of each packed row (prefix position for a prefix row) */
     const int32_t* row_src;            /* [T]   index of the row in user row order (gather map for q) */
+    const int32_t* group_prefix_row_start; /* [G+1] first packed row of each group's prefix rows; they follow all request rows */
+    const int32_t* row_kv_dst;         /* [T]   place of the row's new K/V: d >= 0 row d of the suffix KV arrays, d < 0 row -d-1 of the prefix KV arrays */
     /* Work lists the kernels consume; BLLM_ITEM_INTS int32 per item, fields in
      * the order of bllm_item_field.  Built by fixed rules from the arrays above
      * and the tile constants below. */
@@ -138,6 +143,25 @@ int bllm_prefix_group_create_host(const bllm_layer_desc* desc,
                                   const int32_t* req_suffix_len, const int32_t* req_q_len,
                                   bllm_prefix_groups** out);
 
+/* The general form (Sec. 3.3.1: the common-prefix queue feeds the token batch as
+ * well, a prefix is prefilled before or together with the distinct prompts of its
+ * group).  As bllm_prefix_group_create, plus
+ *   prefix_q_len    host [n_groups] or NULL (all 0): the last prefix_q_len[g]
+ *                   positions of group g's prefix are query rows of this batch
+ *                   ("prefix rows"), 0 <= prefix_q_len[g] <= prefix_len[g].
+ *                   prefix_len[g] counts them: their K/V must be in the prefix KV
+ *                   arrays when the attention runs (bllm_kv_append puts them there).
+ *   host_only       non-zero: as bllm_prefix_group_create_host (hip_stream unused)
+ * A prefix row at position p attends to prefix positions 0 .. p of its group and to
+ * nothing else: the shared-prefix pass computes it with the causal bound, its
+ * suffix part is empty (0, -inf), and the merged result equals the prefix part.
+ * T = sum q_len + sum prefix_q_len rows in every [T, ...] tensor. */
+int bllm_prefix_group_create_ex(const bllm_layer_desc* desc,
+                                int32_t n_groups, const int32_t* prefix_len, const int32_t* prefix_q_len,
+                                int32_t n_requests, const int32_t* req_group,
+                                const int32_t* req_suffix_len, const int32_t* req_q_len,
+                                int host_only, void* hip_stream, bllm_prefix_groups** out);
+
 int bllm_prefix_group_metadata(const bllm_prefix_groups* pg, bllm_packing_view* out);
 int bllm_prefix_group_destroy(bllm_prefix_groups* pg);
 
@@ -191,6 +215,19 @@ int bllm_suffix_attention_merged(const bllm_prefix_groups* pg, const void* q,
                                  const void* k_suffix, const void* v_suffix,
                                  const float* o_prefix, const float* lse_prefix,
                                  void* o_out, float* lse_out, void* hip_stream);
+
+/* Write the new keys and values of the batch's own tokens into the KV memory,
+ * which keeps every shared prefix once per group apart from the distinct parts
+ * of the requests (Sec. 3.3.1, Sec. 3.4): packed row t goes to row row_kv_dst[t]
+ * of the suffix arrays (req_kv_start[request] + position), a prefix row to row
+ * prefix_kv_start[group] + position of the prefix arrays.  Runs before the
+ * attention calls of the layer, on the same stream.  Plain copies, bit exact.
+ *   k_new, v_new        device [T,Hkv,D] desc.dtype, packed order
+ *   k_prefix, v_prefix  device [sum Lp,Hkv,D]  rows of prefix rows are overwritten; may be NULL when the batch has no prefix rows
+ *   k_suffix, v_suffix  device [sum s,Hkv,D]   rows of request rows are overwritten; may be NULL when it has no request rows
+ * All other rows are left as they are.  Allocates nothing. */
+int bllm_kv_append(const bllm_prefix_groups* pg, const void* k_new, const void* v_new,
+                   void* k_prefix, void* v_prefix, void* k_suffix, void* v_suffix, void* hip_stream);
 
 /* The whole path in one call (Sec. 4.3.3: the partial attention on the shared
  * context and on the distinct part, Sec. 5: reduced through online softmax):

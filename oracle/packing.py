@@ -213,10 +213,7 @@ def build_work_lists(meta, prefix_len, req_suffix_len, req_q_len, n_q_heads, n_k
         for t in range(gprs[0]):
             for j in range(n_kv_heads):
                 suffix_rows.append([t, 1, j, rks[row_req[t]], row_pos[t] + 1, row_pos[t] + 1, -1, 0])
-    # prefix rows have no suffix part: empty streaming items write their 0 / -inf
-    for t in range(gprs[0], T):
-        for j in range(n_kv_heads):
-            suffix_rows.append([t, 1, j, 0, 0, 0, -1, 0])
+    # prefix rows have no suffix part and no suffix item
     # prefix tile items: longest KV range first (stable); suffix tile items keep request order
     prefix_tiles.sort(key=lambda it: -it[4])
     # streaming items: longest range first (stable)

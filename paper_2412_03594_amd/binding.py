@@ -15,7 +15,8 @@ _LIB = None
 EXPORTS = ["bllm_prefix_group_create", "bllm_prefix_group_create_host", "bllm_prefix_group_metadata",
            "bllm_prefix_group_destroy", "bllm_shared_prefix_attention", "bllm_suffix_attention", "bllm_lse_merge",
            "bllm_suffix_attention_merged", "bllm_prefix_shared_attention", "bllm_prefix_shared_workspace_bytes",
-           "bllm_identify_prefix_groups", "bllm_last_error", "bllm_version"]
+           "bllm_identify_prefix_groups", "bllm_last_error", "bllm_version", "bllm_prefix_group_create_ex",
+           "bllm_kv_append"]
 
 
 class BllmError(RuntimeError):
@@ -37,6 +38,7 @@ class PackingView(C.Structure):
                 ("perm_req", _I32P), ("req_row_start", _I32P), ("group_req_start", _I32P),
                 ("group_row_start", _I32P), ("group_decode_rows", _I32P), ("prefix_kv_start", _I32P),
                 ("req_kv_start", _I32P), ("row_req", _I32P), ("row_pos", _I32P), ("row_src", _I32P),
+                ("group_prefix_row_start", _I32P), ("row_kv_dst", _I32P),
                 ("n_prefix_tile_items", C.c_int32), ("prefix_tile_items", _I32P),
                 ("n_prefix_row_items", C.c_int32), ("prefix_row_items", _I32P),
                 ("n_suffix_tile_items", C.c_int32), ("suffix_tile_items", _I32P),
@@ -65,6 +67,11 @@ def load_library():
                                              C.c_void_p, C.POINTER(h)]
     lib.bllm_prefix_group_create_host.argtypes = [C.POINTER(LayerDesc), C.c_int32, _I32P, C.c_int32, _I32P, _I32P,
                                                   _I32P, C.POINTER(h)]
+    lib.bllm_prefix_group_create_ex.argtypes = [C.POINTER(LayerDesc), C.c_int32, _I32P, _I32P, C.c_int32, _I32P, _I32P,
+                                                _I32P, C.c_int, C.c_void_p, C.POINTER(h)]
+    lib.bllm_prefix_group_create_ex.restype = C.c_int
+    lib.bllm_kv_append.argtypes = [h] + [C.c_void_p] * 7
+    lib.bllm_kv_append.restype = C.c_int
     lib.bllm_prefix_group_metadata.argtypes = [h, C.POINTER(PackingView)]
     lib.bllm_prefix_group_destroy.argtypes = [h]
     for name in ("bllm_shared_prefix_attention", "bllm_suffix_attention"):
@@ -143,7 +150,8 @@ class PrefixGroups:
              "group_req_start": arr(v.group_req_start, g + 1), "group_row_start": arr(v.group_row_start, g + 1),
              "group_decode_rows": arr(v.group_decode_rows, g), "prefix_kv_start": arr(v.prefix_kv_start, g + 1),
              "req_kv_start": arr(v.req_kv_start, r + 1), "row_req": arr(v.row_req, t), "row_pos": arr(v.row_pos, t),
-             "row_src": arr(v.row_src, t),
+             "row_src": arr(v.row_src, t), "group_prefix_row_start": arr(v.group_prefix_row_start, g + 1),
+             "row_kv_dst": arr(v.row_kv_dst, t),
              "tile_rows": v.tile_rows, "prefix_split_len": v.prefix_split_len,
              "suffix_split_len": v.suffix_split_len, "n_prefix_ws_rows": v.n_prefix_ws_rows,
              "n_suffix_ws_rows": v.n_suffix_ws_rows,
@@ -171,8 +179,10 @@ def _make_desc(n_q_heads, n_kv_heads, head_dim, dtype, softmax_scale=0.0):
     return LayerDesc(int(n_q_heads), int(n_kv_heads), int(head_dim), int(dtype), float(softmax_scale))
 
 
-def prefix_group_create(desc, prefix_len, req_group, req_suffix_len, req_q_len, stream=None, host_only=False):
-    """bllm_prefix_group_create (or bllm_prefix_group_create_host with host_only=True).
+def prefix_group_create(desc, prefix_len, req_group, req_suffix_len, req_q_len, stream=None, host_only=False,
+                        prefix_q_len=None):
+    """bllm_prefix_group_create (or bllm_prefix_group_create_host with host_only=True;
+    bllm_prefix_group_create_ex when prefix_q_len is given).
     desc: LayerDesc or a tuple (n_q_heads, n_kv_heads, head_dim, dtype[, scale])."""
     lib = load_library()
     if not isinstance(desc, LayerDesc):
@@ -184,7 +194,14 @@ def prefix_group_create(desc, prefix_len, req_group, req_suffix_len, req_q_len, 
     if not (len(rg) == len(rs) == len(rq)):
         raise ValueError("request arrays differ in length")
     h = C.c_void_p()
-    if host_only:
+    if prefix_q_len is not None:
+        pq, pqp = _i32(prefix_q_len)
+        if len(pq) != len(pl):
+            raise ValueError("prefix_q_len and prefix_len differ in length")
+        _check(lib.bllm_prefix_group_create_ex(C.byref(desc), len(pl), plp, pqp, len(rg), rgp, rsp, rqp,
+                                               1 if host_only else 0, None if host_only else _stream(stream),
+                                               C.byref(h)))
+    elif host_only:
         _check(lib.bllm_prefix_group_create_host(C.byref(desc), len(pl), plp, len(rg), rgp, rsp, rqp, C.byref(h)))
     else:
         _check(lib.bllm_prefix_group_create(C.byref(desc), len(pl), plp, len(rg), rgp, rsp, rqp, _stream(stream),
@@ -205,6 +222,11 @@ def suffix_attention(pg, q, k_suffix, v_suffix, o_part, lse_part, stream=None):
 def suffix_attention_merged(pg, q, k_suffix, v_suffix, o_prefix, lse_prefix, o_out, lse_out=None, stream=None):
     _check(load_library().bllm_suffix_attention_merged(pg.handle, _ptr(q), _ptr(k_suffix), _ptr(v_suffix), _ptr(o_prefix),
                                                        _ptr(lse_prefix), _ptr(o_out), _ptr(lse_out), _stream(stream)))
+
+
+def kv_append(pg, k_new, v_new, k_prefix, v_prefix, k_suffix, v_suffix, stream=None):
+    _check(load_library().bllm_kv_append(pg.handle, _ptr(k_new), _ptr(v_new), _ptr(k_prefix), _ptr(v_prefix),
+                                         _ptr(k_suffix), _ptr(v_suffix), _stream(stream)))
 
 
 def lse_merge(pg, o_a, lse_a, o_b, lse_b, o_out, lse_out=None, stream=None):

@@ -50,9 +50,9 @@ int hip_fail(hipError_t e, const char* what) {
 
 size_t align256(size_t n) { return (n + 255) & ~static_cast<size_t>(255); }
 
-int create_common(const bllm_layer_desc* desc, int32_t n_groups, const int32_t* prefix_len, int32_t n_requests,
-                  const int32_t* req_group, const int32_t* req_suffix_len, const int32_t* req_q_len,
-                  bllm_prefix_groups** out) {
+int create_common(const bllm_layer_desc* desc, int32_t n_groups, const int32_t* prefix_len,
+                  const int32_t* prefix_q_len, int32_t n_requests, const int32_t* req_group,
+                  const int32_t* req_suffix_len, const int32_t* req_q_len, bllm_prefix_groups** out) {
     if (!out) {
         set_error("null output handle pointer");
         return BLLM_INVALID_ARG;
@@ -67,7 +67,8 @@ int create_common(const bllm_layer_desc* desc, int32_t n_groups, const int32_t* 
     pg->desc = *desc;
     pg->scale = desc->softmax_scale > 0.0f ? desc->softmax_scale : 1.0f / std::sqrt(static_cast<float>(desc->head_dim));
     try {
-        rc = build_packing(*desc, n_groups, prefix_len, n_requests, req_group, req_suffix_len, req_q_len, &pg->pk);
+        rc = build_packing(*desc, n_groups, prefix_len, prefix_q_len, n_requests, req_group, req_suffix_len, req_q_len,
+                           &pg->pk);
     } catch (const std::bad_alloc&) {
         set_error("host allocation failed while packing");
         rc = BLLM_OUT_OF_MEMORY;
@@ -91,10 +92,10 @@ int upload(bllm_prefix_groups* pg, hipStream_t stream) {
     if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
     const size_t row_elems = static_cast<size_t>(pg->desc.n_q_heads) * pg->desc.head_dim;
     const size_t ws_rows = static_cast<size_t>(std::max(p.n_prefix_ws_rows, p.n_suffix_ws_rows));
-    const size_t sizes[8] = {bytes_of(p.prefix_tile_items), bytes_of(p.prefix_row_items), bytes_of(p.suffix_tile_items),
+    const size_t sizes[9] = {bytes_of(p.prefix_tile_items), bytes_of(p.prefix_row_items), bytes_of(p.suffix_tile_items),
                              bytes_of(p.suffix_row_items),  bytes_of(p.prefix_row_split), bytes_of(p.suffix_row_split),
                              align256(ws_rows * row_elems * sizeof(float)),
-                             align256(ws_rows * pg->desc.n_q_heads * sizeof(float))};
+                             align256(ws_rows * pg->desc.n_q_heads * sizeof(float)), bytes_of(p.row_kv_dst)};
     size_t total = 256;
     for (size_t s : sizes) total += s;
     e = hipMalloc(&pg->dev_blob, total);
@@ -114,6 +115,7 @@ int upload(bllm_prefix_groups* pg, hipStream_t stream) {
     pg->d.suffix_row_split = reinterpret_cast<RowSplit*>(place(sizes[5]));
     pg->d.ws_o = reinterpret_cast<float*>(place(sizes[6]));
     pg->d.ws_lse = reinterpret_cast<float*>(place(sizes[7]));
+    pg->d.row_kv_dst = reinterpret_cast<int32_t*>(place(sizes[8]));
 
     auto copy = [&](void* dst, const void* src, size_t n) -> hipError_t {
         if (n == 0) return hipSuccess;
@@ -130,6 +132,7 @@ int upload(bllm_prefix_groups* pg, hipStream_t stream) {
     BLLM_UP(pg->d.suffix_row_items, p.suffix_row_items);
     BLLM_UP(pg->d.prefix_row_split, p.prefix_row_split);
     BLLM_UP(pg->d.suffix_row_split, p.suffix_row_split);
+    BLLM_UP(pg->d.row_kv_dst, p.row_kv_dst);
 #undef BLLM_UP
     // The source vectors are pageable, so the copies above are staged; the
     // synchronisation makes the handle usable from any stream afterwards.
@@ -171,19 +174,30 @@ extern "C" {
 int bllm_prefix_group_create_host(const bllm_layer_desc* desc, int32_t n_groups, const int32_t* prefix_len,
                                   int32_t n_requests, const int32_t* req_group, const int32_t* req_suffix_len,
                                   const int32_t* req_q_len, bllm_prefix_groups** out) {
-    return create_common(desc, n_groups, prefix_len, n_requests, req_group, req_suffix_len, req_q_len, out);
+    return create_common(desc, n_groups, prefix_len, nullptr, n_requests, req_group, req_suffix_len, req_q_len, out);
 }
 
 int bllm_prefix_group_create(const bllm_layer_desc* desc, int32_t n_groups, const int32_t* prefix_len,
                              int32_t n_requests, const int32_t* req_group, const int32_t* req_suffix_len,
                              const int32_t* req_q_len, void* hip_stream, bllm_prefix_groups** out) {
+    return bllm_prefix_group_create_ex(desc, n_groups, prefix_len, nullptr, n_requests, req_group, req_suffix_len,
+                                       req_q_len, 0, hip_stream, out);
+}
+
+int bllm_prefix_group_create_ex(const bllm_layer_desc* desc, int32_t n_groups, const int32_t* prefix_len,
+                                const int32_t* prefix_q_len, int32_t n_requests, const int32_t* req_group,
+                                const int32_t* req_suffix_len, const int32_t* req_q_len, int host_only,
+                                void* hip_stream, bllm_prefix_groups** out) {
     bllm_prefix_groups* pg = nullptr;
-    int rc = create_common(desc, n_groups, prefix_len, n_requests, req_group, req_suffix_len, req_q_len, &pg);
+    int rc = create_common(desc, n_groups, prefix_len, prefix_q_len, n_requests, req_group, req_suffix_len, req_q_len,
+                           &pg);
     if (rc != BLLM_OK) return rc;
-    rc = upload(pg, static_cast<hipStream_t>(hip_stream));
-    if (rc != BLLM_OK) {
-        bllm_prefix_group_destroy(pg);
-        return rc;
+    if (!host_only) {
+        rc = upload(pg, static_cast<hipStream_t>(hip_stream));
+        if (rc != BLLM_OK) {
+            bllm_prefix_group_destroy(pg);
+            return rc;
+        }
     }
     *out = pg;
     return BLLM_OK;
@@ -210,6 +224,8 @@ int bllm_prefix_group_metadata(const bllm_prefix_groups* pg, bllm_packing_view* 
     v->row_req = p.row_req.data();
     v->row_pos = p.row_pos.data();
     v->row_src = p.row_src.data();
+    v->group_prefix_row_start = p.group_prefix_row_start.data();
+    v->row_kv_dst = p.row_kv_dst.data();
     v->n_prefix_tile_items = static_cast<int32_t>(p.prefix_tile_items.size());
     v->prefix_tile_items = reinterpret_cast<const int32_t*>(p.prefix_tile_items.data());
     v->n_prefix_row_items = static_cast<int32_t>(p.prefix_row_items.size());
@@ -265,6 +281,12 @@ static int launch_pass_kernels(const bllm_prefix_groups* pg, bool prefix, const 
                                     static_cast<int32_t>(rows.size()), prefix ? p.prefix_stream_wpi : p.suffix_stream_wpi, q, k, v,
                                     o_part, lse_part, pg->d.ws_o, pg->d.ws_lse, mt);
         if (e != hipSuccess) return hip_fail(e, "streaming attention launch");
+    }
+    if (!prefix) {
+        // prefix rows (they follow all request rows) have no suffix part
+        const int32_t row0 = p.group_prefix_row_start[0];
+        e = launch_keyless_rows(c, row0, p.n_rows - row0, o_part, lse_part, mt);
+        if (e != hipSuccess) return hip_fail(e, "keyless rows launch");
     }
     return BLLM_OK;
 }
@@ -325,6 +347,23 @@ int bllm_lse_merge(const bllm_prefix_groups* pg, const float* o_a, const float* 
     LaunchCtx c = make_ctx(pg, hip_stream);
     hipError_t e = launch_lse_merge(c, o_a, lse_a, o_b, lse_b, o_out, lse_out);
     if (e != hipSuccess) return hip_fail(e, "lse merge launch");
+    return BLLM_OK;
+}
+
+int bllm_kv_append(const bllm_prefix_groups* pg, const void* k_new, const void* v_new, void* k_prefix, void* v_prefix,
+                   void* k_suffix, void* v_suffix, void* hip_stream) {
+    int rc = check_device_call(pg, {k_new, v_new});
+    if (rc != BLLM_OK) return rc;
+    const Packing& p = pg->pk;
+    const bool any_prefix = p.group_prefix_row_start[p.n_groups] > p.group_prefix_row_start[0];
+    const bool any_suffix = p.group_prefix_row_start[0] > 0;
+    if ((any_prefix && (!k_prefix || !v_prefix)) || (any_suffix && (!k_suffix || !v_suffix))) {
+        set_error("null KV array that rows of this batch belong to");
+        return BLLM_INVALID_ARG;
+    }
+    const hipError_t e = launch_kv_append(make_ctx(pg, hip_stream), pg->d.row_kv_dst, k_new, v_new, k_prefix, v_prefix,
+                                          k_suffix, v_suffix);
+    if (e != hipSuccess) return hip_fail(e, "kv append launch");
     return BLLM_OK;
 }
 

@@ -35,7 +35,7 @@ struct RowSplit {
 struct Packing {
     int32_t n_groups = 0, n_requests = 0, n_rows = 0, n_active = 0;
     std::vector<int32_t> perm_req, req_row_start, group_req_start, group_row_start, group_decode_rows,
-        prefix_kv_start, req_kv_start, row_req, row_pos, row_src;
+        prefix_kv_start, req_kv_start, row_req, row_pos, row_src, group_prefix_row_start, row_kv_dst;
     std::vector<Item> prefix_tile_items, prefix_row_items, suffix_tile_items, suffix_row_items;
     std::vector<RowSplit> prefix_row_split, suffix_row_split;
     int32_t tile_rows = 0, prefix_split_len = 0, suffix_split_len = 0;
@@ -54,6 +54,7 @@ struct DeviceLists {
     Item* suffix_row_items = nullptr;
     RowSplit* prefix_row_split = nullptr;
     RowSplit* suffix_row_split = nullptr;
+    int32_t* row_kv_dst = nullptr;
     float* ws_o = nullptr;     // [ws_rows, Hq, D]
     float* ws_lse = nullptr;   // [ws_rows, Hq]
 };
@@ -75,7 +76,8 @@ namespace bllm {
 void set_error(const std::string& msg);
 
 // packing (host)
-int build_packing(const bllm_layer_desc& desc, int32_t n_groups, const int32_t* prefix_len, int32_t n_requests,
+int build_packing(const bllm_layer_desc& desc, int32_t n_groups, const int32_t* prefix_len,
+                  const int32_t* prefix_q_len /* may be null: no prefix rows */, int32_t n_requests,
                   const int32_t* req_group, const int32_t* req_suffix_len, const int32_t* req_q_len, Packing* out);
 
 // Kernel launchers (bllm_kernels.hip).  All return hipError_t of the launch.
@@ -110,6 +112,14 @@ hipError_t launch_tile_attention(const LaunchCtx& c, const Item* items, int32_t 
                                  float* ws_lse, const MergeTarget& mt);
 hipError_t launch_split_combine(const LaunchCtx& c, const RowSplit* row_split, const float* ws_o, const float* ws_lse,
                                 float* o_part, float* lse_part);
+// Copies row t of k_new / v_new ([n_rows, Hkv, D], layer dtype) to row row_kv_dst[t] of the suffix arrays,
+// or row -row_kv_dst[t] - 1 of the prefix arrays when negative.
+hipError_t launch_kv_append(const LaunchCtx& c, const int32_t* row_kv_dst, const void* k_new, const void* v_new,
+                            void* k_prefix, void* v_prefix, void* k_suffix, void* v_suffix);
+// Rows row0 .. row0 + n_rows - 1 have no keys in this pass: writes their partial (0, -inf), or with a
+// merge target the other part's result as the final output.  The other part of such a row is never split.
+hipError_t launch_keyless_rows(const LaunchCtx& c, int32_t row0, int32_t n_rows, float* o_part, float* lse_part,
+                               const MergeTarget& mt);
 hipError_t launch_lse_merge(const LaunchCtx& c, const float* o_a, const float* lse_a, const float* o_b,
                             const float* lse_b, void* o_out, float* lse_out);
 

@@ -25,8 +25,9 @@ int32_t ceil_div(int32_t a, int32_t b) { return (a + b - 1) / b; }
 
 }  // namespace
 
-int build_packing(const bllm_layer_desc& desc, int32_t n_groups, const int32_t* prefix_len, int32_t n_requests,
-                  const int32_t* req_group, const int32_t* req_suffix_len, const int32_t* req_q_len, Packing* out) {
+int build_packing(const bllm_layer_desc& desc, int32_t n_groups, const int32_t* prefix_len,
+                  const int32_t* prefix_q_len, int32_t n_requests, const int32_t* req_group,
+                  const int32_t* req_suffix_len, const int32_t* req_q_len, Packing* out) {
     if (n_groups < 1 || n_requests < 0) {
         set_error("n_groups must be >= 1 and n_requests >= 0");
         return BLLM_INVALID_ARG;
@@ -56,6 +57,10 @@ int build_packing(const bllm_layer_desc& desc, int32_t n_groups, const int32_t* 
             return BLLM_INVALID_ARG;
         }
         p.prefix_kv_start[g + 1] = static_cast<int32_t>(acc);
+        if (prefix_q_len && (prefix_q_len[g] < 0 || prefix_q_len[g] > prefix_len[g])) {
+            set_error("group " + std::to_string(g) + ": need 0 <= prefix_q_len <= prefix_len");
+            return BLLM_INVALID_ARG;
+        }
     }
     p.req_kv_start.assign(n_requests + 1, 0);
     std::vector<int32_t> user_row_start(n_requests + 1, 0);
@@ -77,6 +82,17 @@ int build_packing(const bllm_layer_desc& desc, int32_t n_groups, const int32_t* 
         }
         p.req_kv_start[r + 1] = static_cast<int32_t>(kv_acc);
         user_row_start[r + 1] = static_cast<int32_t>(row_acc);
+    }
+    const int32_t n_request_rows = static_cast<int32_t>(row_acc);
+    // Rows of prefixes that are prefilled in this iteration follow all request rows, group by group.
+    p.group_prefix_row_start.assign(n_groups + 1, n_request_rows);
+    for (int32_t g = 0; g < n_groups; ++g) {
+        row_acc += prefix_q_len ? prefix_q_len[g] : 0;
+        if (!fits_i32(row_acc * desc.n_q_heads)) {
+            set_error("query rows overflow int32");
+            return BLLM_INVALID_ARG;
+        }
+        p.group_prefix_row_start[g + 1] = static_cast<int32_t>(row_acc);
     }
     p.n_rows = static_cast<int32_t>(row_acc);
 
@@ -112,6 +128,7 @@ int build_packing(const bllm_layer_desc& desc, int32_t n_groups, const int32_t* 
     p.row_req.resize(p.n_rows);
     p.row_pos.resize(p.n_rows);
     p.row_src.resize(p.n_rows);
+    p.row_kv_dst.resize(p.n_rows);
     int32_t t = 0;
     for (int32_t a = 0; a < p.n_active; ++a) {
         const int32_t r = p.perm_req[a];
@@ -121,12 +138,22 @@ int build_packing(const bllm_layer_desc& desc, int32_t n_groups, const int32_t* 
             p.row_req[t] = r;
             p.row_pos[t] = first_pos + i;
             p.row_src[t] = user_row_start[r] + i;
+            p.row_kv_dst[t] = p.req_kv_start[r] + first_pos + i;
         }
         p.req_row_start[a + 1] = t;
     }
     p.group_row_start.assign(n_groups + 1, 0);
     for (int32_t g = 0; g < n_groups; ++g) p.group_row_start[g] = p.req_row_start[p.group_req_start[g]];
-    p.group_row_start[n_groups] = p.n_rows;
+    p.group_row_start[n_groups] = n_request_rows;
+    for (int32_t g = 0; g < n_groups; ++g) {
+        const int32_t n = p.group_prefix_row_start[g + 1] - p.group_prefix_row_start[g];
+        for (int32_t i = 0; i < n; ++i, ++t) {
+            p.row_req[t] = -1;
+            p.row_pos[t] = prefix_len[g] - n + i;
+            p.row_src[t] = t;
+            p.row_kv_dst[t] = -(p.prefix_kv_start[g] + p.row_pos[t]) - 1;
+        }
+    }
 
     // ---- work lists --------------------------------------------------------------------------
     const bool mfma = desc.dtype == BLLM_BF16 && desc.head_dim == 128;
@@ -141,6 +168,7 @@ int build_packing(const bllm_layer_desc& desc, int32_t n_groups, const int32_t* 
         int32_t max_lp = 0;
         for (int32_t g = 0; g < n_groups; ++g) {
             const int32_t rows = p.group_row_start[g + 1] - p.group_row_start[g];
+            base_items += static_cast<int64_t>(ceil_div(p.group_prefix_row_start[g + 1] - p.group_prefix_row_start[g], br)) * n_kv_heads;
             if (rows == 0 || prefix_len[g] == 0) continue;
             base_items += static_cast<int64_t>(ceil_div(rows, br)) * n_kv_heads;
             max_lp = std::max(max_lp, prefix_len[g]);
@@ -154,6 +182,17 @@ int build_packing(const bllm_layer_desc& desc, int32_t n_groups, const int32_t* 
         }
         int64_t ws_rows = 0;
         for (int32_t g = 0; g < n_groups; ++g) {
+            // Prefix rows: causal inside the prefix (row i sees the positions up to its own),
+            // never split, written directly.
+            const int32_t prow0 = p.group_prefix_row_start[g];
+            const int32_t n_pre = p.group_prefix_row_start[g + 1] - prow0;
+            for (int32_t i0 = 0; i0 < n_pre; i0 += br) {
+                const int32_t n = std::min(br, n_pre - i0);
+                const int32_t first_vis = prefix_len[g] - n_pre + i0 + 1;
+                for (int32_t j = 0; j < n_kv_heads; ++j)
+                    p.prefix_tile_items.push_back(
+                        Item{prow0 + i0, n, j, p.prefix_kv_start[g], first_vis + n - 1, first_vis, -1, 0});
+            }
             const int32_t row0 = p.group_row_start[g];
             const int32_t rows = p.group_row_start[g + 1] - row0;
             if (rows == 0) continue;
@@ -214,13 +253,19 @@ int build_packing(const bllm_layer_desc& desc, int32_t n_groups, const int32_t* 
                 for (int32_t j = 0; j < n_kv_heads; ++j)
                     p.prefix_row_items.push_back(
                         Item{tt, 1, j, p.prefix_kv_start[g], prefix_len[g], prefix_len[g], -1, 0});
+            for (int32_t tt = p.group_prefix_row_start[g]; tt < p.group_prefix_row_start[g + 1]; ++tt)
+                for (int32_t j = 0; j < n_kv_heads; ++j)
+                    p.prefix_row_items.push_back(
+                        Item{tt, 1, j, p.prefix_kv_start[g], p.row_pos[tt] + 1, p.row_pos[tt] + 1, -1, 0});
         }
-        for (int32_t tt = 0; tt < p.n_rows; ++tt) {
+        for (int32_t tt = 0; tt < n_request_rows; ++tt) {
             const int32_t r = p.row_req[tt];
             for (int32_t j = 0; j < n_kv_heads; ++j)
                 p.suffix_row_items.push_back(Item{tt, 1, j, p.req_kv_start[r], p.row_pos[tt] + 1, p.row_pos[tt] + 1, -1, 0});
         }
     }
+    // Prefix rows have no suffix part and no suffix item: the suffix pass writes their (0, -inf) - or,
+    // merging, hands the prefix result on - with a plain streaming kernel over that row range.
     // Streaming items: longest first, so that the hardware's in-order workgroup dispatch
     // balances the ragged lengths; then pick how many wavefronts share an item from the
     // mean range length (about 64 KV rows or more per wavefront).

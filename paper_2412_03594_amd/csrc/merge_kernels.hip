@@ -43,6 +43,32 @@ __global__ __launch_bounds__(kMergeThreads) void lse_merge_kernel(
     if (lse_out != nullptr && quad == 0) lse_out[rh] = w.lse;
 }
 
+// Rows that have no keys in a pass (the prefix rows in the distinct-suffix pass): the pass's
+// partial is (0, -inf); merging, the final output is the other part's result converted to
+// the layer's dtype.  Rows row0 .. of the [n_rows, Hq, D] tensors; rh counts from row0 * Hq.
+template <bool kBf16Out>
+__global__ __launch_bounds__(kMergeThreads) void keyless_rows_kernel(
+    const float* __restrict__ o_a, const float* __restrict__ lse_a, void* __restrict__ o_out,
+    float* __restrict__ lse_out, float* __restrict__ o_part, float* __restrict__ lse_part, int64_t rh0,
+    int64_t n_row_heads, int quads_per_row_head) {
+    const int64_t gid = static_cast<int64_t>(blockIdx.x) * kMergeThreads + threadIdx.x;
+    const int64_t rel = gid / quads_per_row_head;
+    if (rel >= n_row_heads) return;
+    const int64_t rh = rh0 + rel;
+    const int quad = static_cast<int>(gid - rel * quads_per_row_head);
+    const size_t off = static_cast<size_t>(rh) * quads_per_row_head * 4 + quad * 4;
+    if (o_a != nullptr) {
+        const float4 r = load_once(o_a + off);
+        const float l = lse_a[rh];
+        const bool empty = l == -INFINITY;       // an empty other part: its rows are not read as values
+        store_out4<kBf16Out>(o_out, off, empty ? 0.f : r.x, empty ? 0.f : r.y, empty ? 0.f : r.z, empty ? 0.f : r.w);
+        if (lse_out != nullptr && quad == 0) lse_out[rh] = l;
+    } else {
+        *reinterpret_cast<float4*>(o_part + off) = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (quad == 0) lse_part[rh] = -INFINITY;
+    }
+}
+
 __global__ __launch_bounds__(kMergeThreads) void split_combine_kernel(
     const RowSplit* __restrict__ row_split, const float* __restrict__ ws_o, const float* __restrict__ ws_lse,
     float* __restrict__ o_part, float* __restrict__ lse_part, int64_t n_row_heads, int n_q_heads,
@@ -122,6 +148,23 @@ hipError_t launch_lse_merge(const LaunchCtx& c, const float* o_a, const float* l
     else
         hipLaunchKernelGGL(lse_merge_kernel<false>, grid, block, 0, c.stream, o_a, lse_a, o_b, lse_b, o_out, lse_out,
                            n_row_heads, quads);
+    return hipGetLastError();
+}
+
+hipError_t launch_keyless_rows(const LaunchCtx& c, int32_t row0, int32_t n_rows, float* o_part, float* lse_part,
+                               const MergeTarget& mt) {
+    const int64_t n_row_heads = static_cast<int64_t>(n_rows) * c.desc->n_q_heads;
+    const int quads = c.desc->head_dim / 4;
+    const int64_t threads = n_row_heads * quads;
+    if (threads == 0) return hipSuccess;
+    const int64_t rh0 = static_cast<int64_t>(row0) * c.desc->n_q_heads;
+    dim3 grid(static_cast<unsigned>((threads + kMergeThreads - 1) / kMergeThreads)), block(kMergeThreads);
+    if (c.desc->dtype == BLLM_BF16)
+        hipLaunchKernelGGL(keyless_rows_kernel<true>, grid, block, 0, c.stream, mt.o_a, mt.lse_a, mt.o_out, mt.lse_out,
+                           o_part, lse_part, rh0, n_row_heads, quads);
+    else
+        hipLaunchKernelGGL(keyless_rows_kernel<false>, grid, block, 0, c.stream, mt.o_a, mt.lse_a, mt.o_out, mt.lse_out,
+                           o_part, lse_part, rh0, n_row_heads, quads);
     return hipGetLastError();
 }
 

@@ -10,7 +10,10 @@ def layer_tuple(L, scale=0.0):
     return (L.n_q_heads, L.n_kv_heads, L.head_dim, L.dtype, scale)
 
 
-def run_hip_path(batch, vals, scale=0.0, want_lse=True, pg=None):
+def run_hip_path(batch, vals, scale=0.0, want_lse=True, pg=None, append=False):
+    """append=True: the K/V rows of the batch's own tokens are blanked (NaN) in the uploaded KV
+    arrays and put back by bllm_kv_append before the attention calls; out["kv"] then holds the
+    four KV arrays as they were on the device afterwards."""
     import torch
     import paper_2412_03594_amd as bllm
     L = batch.layer
@@ -19,12 +22,24 @@ def run_hip_path(batch, vals, scale=0.0, want_lse=True, pg=None):
     own = pg is None
     if own:
         pg = bllm.prefix_group_create(layer_tuple(L, scale), batch.prefix_len, batch.req_group,
-                                      batch.req_suffix_len, batch.req_q_len)
+                                      batch.req_suffix_len, batch.req_q_len, prefix_q_len=batch.prefix_q_len)
     meta = pg.metadata()
     T = meta["n_rows"]
     up = lambda x: torch.from_numpy(np.ascontiguousarray(x)).to(dev).to(tdt).contiguous()
     q = up(vals["q"][meta["row_src"]])
-    kp, vp, ks, vs = up(vals["k_prefix"]), up(vals["v_prefix"]), up(vals["k_suffix"]), up(vals["v_suffix"])
+    kv_host = {k: vals[k] for k in ("k_prefix", "v_prefix", "k_suffix", "v_suffix")}
+    if append:
+        kv_host = {k: a.copy() for k, a in kv_host.items()}
+        k_new = np.zeros((T, L.n_kv_heads, L.head_dim), np.float32)
+        v_new = np.zeros_like(k_new)
+        for t, d in enumerate(meta["row_kv_dst"]):
+            side, row = ("suffix", d) if d >= 0 else ("prefix", -d - 1)
+            k_new[t], v_new[t] = vals["k_" + side][row], vals["v_" + side][row]
+            kv_host["k_" + side][row] = np.nan
+            kv_host["v_" + side][row] = np.nan
+    kp, vp, ks, vs = (up(kv_host[k]) for k in ("k_prefix", "v_prefix", "k_suffix", "v_suffix"))
+    if append:
+        bllm.kv_append(pg, up(k_new), up(v_new), kp, vp, ks, vs)
     nan = float("nan")
     o1 = torch.full((T, L.n_q_heads, L.head_dim), nan, device=dev, dtype=torch.float32)
     o2 = torch.full_like(o1, nan)
@@ -50,6 +65,9 @@ def run_hip_path(batch, vals, scale=0.0, want_lse=True, pg=None):
     back = lambda t: t.float().cpu().numpy()[inv] if T > 0 else t.float().cpu().numpy()
     out = {"o": back(o), "o_prefix": back(o1), "lse_prefix": back(l1), "o_suffix": back(o2), "lse_suffix": back(l2),
            "meta": meta}
+    if append:
+        out["kv"] = {"k_prefix": kp.float().cpu().numpy(), "v_prefix": vp.float().cpu().numpy(),
+                     "k_suffix": ks.float().cpu().numpy(), "v_suffix": vs.float().cpu().numpy()}
     out["o_fused"] = back(o_f)
     out["o_one_call"] = back(o_c)
     if want_lse:
@@ -67,7 +85,7 @@ def run_oracle(batch, vals, scale=None, **kw):
     return oa.prefix_shared_attention(
         vals["q"], vals["k_prefix"], vals["v_prefix"], vals["k_suffix"], vals["v_suffix"],
         batch.prefix_len, batch.req_group, batch.req_suffix_len, batch.req_q_len,
-        L.n_q_heads, L.n_kv_heads, scale=scale, **kw)
+        L.n_q_heads, L.n_kv_heads, scale=scale, prefix_q_len=batch.prefix_q_len, **kw)
 
 
 def max_abs_err(got, ref, rows=None):

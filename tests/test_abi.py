@@ -14,7 +14,8 @@ from paper_2412_03594_amd import binding
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 PACK_KEYS = ["n_rows", "n_active", "perm_req", "req_row_start", "group_req_start", "group_row_start",
-             "group_decode_rows", "prefix_kv_start", "req_kv_start", "row_req", "row_pos", "row_src"]
+             "group_decode_rows", "prefix_kv_start", "req_kv_start", "row_req", "row_pos", "row_src",
+             "group_prefix_row_start", "row_kv_dst"]
 
 
 def test_library_exports_every_declared_symbol():
@@ -30,7 +31,7 @@ def test_library_exports_every_declared_symbol():
 def host_pack(b, **kw):
     L = b.layer
     return bllm.prefix_group_create((L.n_q_heads, L.n_kv_heads, L.head_dim, L.dtype), b.prefix_len, b.req_group,
-                                    b.req_suffix_len, b.req_q_len, host_only=True, **kw)
+                                    b.req_suffix_len, b.req_q_len, host_only=True, prefix_q_len=b.prefix_q_len, **kw)
 
 
 @pytest.mark.parametrize("name", ["tiny_fp32", "l8b_decode", "l8b_mixed", "l8b_mixed_full", "rank_longprefix",
@@ -47,8 +48,10 @@ def test_packing_bit_exact_on_configs(name, shuffle):
 @pytest.mark.parametrize("seed", range(30))
 def test_packing_bit_exact_ragged(seed):
     b = workload.ragged_toy(seed, n_groups=5, max_group=8)
+    if seed % 2:
+        b = workload.with_prefix_prefill(b, seed=seed)
     m = host_pack(b).metadata()
-    ref = pack_token_batch(b.prefix_len, b.req_group, b.req_suffix_len, b.req_q_len)
+    ref = pack_token_batch(b.prefix_len, b.req_group, b.req_suffix_len, b.req_q_len, b.prefix_q_len)
     for k in PACK_KEYS:
         assert np.array_equal(np.asarray(m[k]), np.asarray(ref[k])), k
 
@@ -102,7 +105,7 @@ def check_work_lists(b):
     from oracle.packing import build_work_lists
     L = b.layer
     m = host_pack(b).metadata()
-    ref_meta = pack_token_batch(b.prefix_len, b.req_group, b.req_suffix_len, b.req_q_len)
+    ref_meta = pack_token_batch(b.prefix_len, b.req_group, b.req_suffix_len, b.req_q_len, b.prefix_q_len)
     ref = build_work_lists(ref_meta, b.prefix_len, b.req_suffix_len, b.req_q_len, L.n_q_heads, L.n_kv_heads,
                            L.head_dim, L.dtype == workload.BF16, m["tile_rows"])
     for k in WORK_KEYS:
@@ -124,6 +127,70 @@ def test_work_lists_bit_exact_ragged(seed):
     check_work_lists(workload.ragged_toy(seed, dtype=workload.BF16, n_q_heads=8, n_kv_heads=2, head_dim=128,
                                          n_groups=4, max_prefix=700, max_group=6, max_suffix=200, max_chunk=150))
     check_work_lists(workload.ragged_toy(seed, n_q_heads=4, n_kv_heads=2, head_dim=64))
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_work_lists_bit_exact_with_prefix_rows(seed):
+    big = workload.ragged_toy(seed, dtype=workload.BF16, n_q_heads=8, n_kv_heads=2, head_dim=128, n_groups=4,
+                              max_prefix=700, max_group=6, max_suffix=200, max_chunk=150)
+    m = check_work_lists(workload.with_prefix_prefill(big, seed=seed, max_rows=300 if seed % 2 else None))
+    assert m["group_prefix_row_start"][-1] > m["group_prefix_row_start"][0]
+    check_work_lists(workload.with_prefix_prefill(workload.ragged_toy(seed, n_q_heads=4, n_kv_heads=2, head_dim=64),
+                                                  seed=seed))
+
+
+def test_prefix_only_batch_and_decode_config_with_prefill():
+    """A batch that holds nothing but prefix chunks (the first iterations of a job), and the
+    headline decode batch with one more group whose prefix is prefilled in 2048-row chunks."""
+    L = workload.Layer(32, 8, 128, workload.BF16)
+    only = workload.Batch("prefix_only", L, np.array([4096, 700], np.int32), np.zeros(0, np.int32),
+                          np.zeros(0, np.int32), np.zeros(0, np.int32), prefix_q_len=np.array([2048, 700], np.int32))
+    m = check_work_lists(only)
+    assert m["n_rows"] == 2748 and m["n_active"] == 0 and m["prefix_split_len"] == 0
+    assert len(m["suffix_tile_items"]) == 0 and len(m["suffix_row_items"]) == 0
+    d = workload.l8b_decode(0)
+    grown = workload.Batch("decode+prefill", d.layer, np.append(d.prefix_len, 4096).astype(np.int32), d.req_group,
+                           d.req_suffix_len, d.req_q_len, prefix_q_len=np.append(np.zeros(d.n_groups), 2048).astype(np.int32))
+    check_work_lists(grown)
+
+
+def test_prefix_rows_validation():
+    mk = lambda pl, pq: bllm.prefix_group_create((8, 2, 128, bllm.BF16), pl, [0], [3], [1], host_only=True,
+                                                 prefix_q_len=pq)
+    mk([4], [4]).destroy()
+    for bad in ([5], [-1]):
+        with pytest.raises(bllm.BllmError) as e:
+            mk([4], bad)
+        assert e.value.code == -1 and "prefix_q_len" in str(e.value)
+    with pytest.raises(ValueError):
+        mk([4], [1, 1])
+
+
+def test_work_items_with_prefix_rows_cover_every_row_head_once():
+    """Prefix rows: one prefix item per (row, KV head) whose causal bound is the row's own position;
+    no suffix item."""
+    big = workload.ragged_toy(3, dtype=workload.BF16, n_q_heads=8, n_kv_heads=2, head_dim=128, n_groups=4,
+                              max_prefix=700, max_group=6, max_suffix=200, max_chunk=150)
+    b = workload.with_prefix_prefill(big, seed=1)
+    m = host_pack(b).metadata()
+    T, H = m["n_rows"], b.layer.n_kv_heads
+    first_prefix_row = m["group_prefix_row_start"][0]
+    row_group = np.concatenate([b.req_group[m["row_req"][:first_prefix_row]],
+                                np.repeat(np.arange(b.n_groups), np.diff(m["group_prefix_row_start"]))])
+    want = np.where(np.arange(T) < first_prefix_row, b.prefix_len[row_group], m["row_pos"] + 1)
+    sees = np.zeros((T, H), dtype=np.int64)
+    for it in m["prefix_tile_items"]:
+        assert it[3] >= m["prefix_kv_start"][row_group[it[0]]]
+        for i in range(it[1]):
+            sees[it[0] + i, it[2]] += min(it[4], it[5] + i)
+    assert np.array_equal(sees, np.repeat(want[:, None], H, axis=1))
+    seen = np.zeros((T, H), dtype=np.int64)
+    for it in list(m["suffix_tile_items"]) + list(m["suffix_row_items"]):
+        for i in range(it[1]):
+            t = it[0] + i
+            assert t < first_prefix_row and min(it[4], it[5] + i) == m["row_pos"][t] + 1
+            seen[t, it[2]] += 1
+    assert np.all(seen[:first_prefix_row] == 1)
 
 
 def test_work_items_cover_every_row_head_once():

@@ -9,9 +9,13 @@ from helpers import TOL, layer_tuple, max_abs_err, run_hip_path, run_oracle
 pytestmark = pytest.mark.gpu
 
 
-def check_all(batch, vals, scale=0.0, rows=None, requests=None):
-    got = run_hip_path(batch, vals, scale=scale)
-    ref = run_oracle(batch, vals, scale=(scale or None), requests=requests)
+def check_all(batch, vals, scale=0.0, rows=None, requests=None, prefix_groups=None, append=False):
+    got = run_hip_path(batch, vals, scale=scale, append=append)
+    ref = run_oracle(batch, vals, scale=(scale or None), requests=requests, prefix_groups=prefix_groups)
+    if append:
+        # the appended K/V rows are copies: the KV memory is bit for bit what the reference's is
+        for name in ("k_prefix", "v_prefix", "k_suffix", "v_suffix"):
+            assert np.array_equal(got["kv"][name], vals[name]), name
     tol = TOL[batch.layer.dtype]
     errs = {k: max_abs_err(got[k], ref[k], rows) for k in
             ("o", "lse", "o_prefix", "lse_prefix", "o_suffix", "lse_suffix")}
@@ -296,4 +300,113 @@ def test_merge_kernel_alone_with_empty_parts():
     ro, rl = lse_merge(np.nan_to_num(oa_.astype(np.float64)), la, ob_, lb)
     assert max_abs_err(o.cpu().numpy(), ro) <= 1e-5
     assert max_abs_err(l.cpu().numpy(), rl) <= 1e-5
+    pg.destroy()
+
+
+# ------------------------------------ prefix rows and KV append (Sec. 3.3.1) ----
+
+@pytest.mark.parametrize("seed", range(6))
+def test_prefix_rows_ragged_fp32(seed):
+    b = workload.with_prefix_prefill(workload.ragged_toy(seed), seed=seed)
+    check_all(b, workload.draw_values(b), append=True)
+
+
+@pytest.mark.parametrize("seed,hq,hkv,max_rows", [(0, 8, 2, None), (1, 8, 1, 100), (2, 4, 4, None), (3, 32, 8, 70),
+                                                  (4, 64, 8, None)])
+def test_prefix_rows_ragged_bf16_mfma(seed, hq, hkv, max_rows):
+    """Prefix chunks on the matrix-core path: causal tiles inside the prefix, several row blocks,
+    ragged tails; request rows of the same groups in the same batch."""
+    big = workload.ragged_toy(seed, dtype=workload.BF16, n_q_heads=hq, n_kv_heads=hkv, head_dim=128,
+                              n_groups=4, max_prefix=300, max_group=6, max_suffix=200, max_chunk=150)
+    b = workload.with_prefix_prefill(big, seed=seed, max_rows=max_rows)
+    check_all(b, workload.draw_values(b), append=True)
+
+
+def test_prefix_rows_bf16_d64_streams():
+    b = workload.with_prefix_prefill(workload.ragged_toy(1, dtype=workload.BF16, n_q_heads=8, n_kv_heads=2, head_dim=64),
+                                     seed=1)
+    check_all(b, workload.draw_values(b), append=True)
+
+
+def test_prefix_only_batch():
+    """The first iterations of a job: nothing but prefix chunks (one whole prefix, one later chunk)."""
+    L = workload.Layer(32, 8, 128, workload.BF16)
+    b = workload.Batch("prefix_only", L, np.array([1500, 700], np.int32), np.zeros(0, np.int32), np.zeros(0, np.int32),
+                       np.zeros(0, np.int32), prefix_q_len=np.array([600, 700], np.int32))
+    check_all(b, workload.draw_values(b, seed=5), append=True)
+
+
+def test_decode_batch_with_a_prefix_chunk_sampled():
+    """The headline decode batch plus one more group whose 4096-token prefix gets its second
+    2048-row chunk in the same iteration.  The prefix rows of the new group are checked at
+    sampled positions through a prefix that is cut to the sample (causal rows do not see later keys)."""
+    d = workload.l8b_decode(0)
+    b = workload.Batch("decode+prefill", d.layer, np.append(d.prefix_len, 4096).astype(np.int32), d.req_group,
+                       d.req_suffix_len, d.req_q_len,
+                       prefix_q_len=np.append(np.zeros(d.n_groups), 2048).astype(np.int32))
+    v = workload.draw_values(b)
+    got = run_hip_path(b, v, append=True)
+    for name in ("k_prefix", "v_prefix", "k_suffix", "v_suffix"):
+        assert np.array_equal(got["kv"][name], v[name]), name
+    rng = np.random.default_rng(0)
+    reqs = rng.choice(b.n_requests, 6, replace=False)
+    ref = run_oracle(b, v, requests=reqs)
+    row0 = np.concatenate([[0], np.cumsum(b.req_q_len)])
+    rows = np.concatenate([np.arange(row0[r], row0[r + 1]) for r in reqs])
+    tol = TOL[workload.BF16]
+    for k in ("o", "o_fused", "o_one_call"):
+        assert max_abs_err(got[k], ref["o"], rows) <= tol, k
+    for k in ("lse", "lse_fused", "lse_one_call"):
+        assert max_abs_err(got[k], ref["lse"], rows) <= 1e-4, k
+    # sampled prefix rows: position p of the new group is the only query row of a one-group batch
+    # whose prefix ends at p
+    k0 = int(b.prefix_len[:-1].sum())
+    for i in np.concatenate([rng.choice(2048, 24, replace=False), [0, 2047]]):
+        pos = 2048 + int(i)
+        t = b.n_request_rows + int(i)
+        one = workload.Batch("row", b.layer, np.array([pos + 1], np.int32), np.zeros(0, np.int32), np.zeros(0, np.int32),
+                             np.zeros(0, np.int32), prefix_q_len=np.array([1], np.int32))
+        r1 = run_oracle(one, dict(q=v["q"][t:t + 1], k_prefix=v["k_prefix"][k0:k0 + pos + 1],
+                                  v_prefix=v["v_prefix"][k0:k0 + pos + 1], k_suffix=v["k_suffix"][:0],
+                                  v_suffix=v["v_suffix"][:0]))
+        for k in ("o", "o_fused", "o_one_call"):
+            assert max_abs_err(got[k][t:t + 1], r1["o"]) <= tol, (k, pos)
+        for k in ("lse", "lse_fused", "lse_one_call", "lse_prefix"):
+            assert max_abs_err(got[k][t:t + 1], r1["lse"]) <= 1e-4, (k, pos)
+        assert max_abs_err(got["o_prefix"][t:t + 1], r1["o"]) <= 1e-2
+    pre = np.arange(b.n_request_rows, b.n_rows)
+    assert np.all(got["o_suffix"][pre] == 0) and np.all(np.isneginf(got["lse_suffix"][pre]))
+
+
+def test_kv_append_leaves_other_rows_alone_and_validates():
+    import torch
+    import paper_2412_03594_amd as bllm
+    b = workload.with_prefix_prefill(workload.ragged_toy(2, dtype=workload.BF16, n_q_heads=8, n_kv_heads=2,
+                                                         head_dim=128), seed=2)
+    L = b.layer
+    pg = bllm.prefix_group_create(layer_tuple(L), b.prefix_len, b.req_group, b.req_suffix_len, b.req_q_len,
+                                  prefix_q_len=b.prefix_q_len)
+    m = pg.metadata()
+    dev = torch.device("cuda:0")
+    T = m["n_rows"]
+    g = torch.Generator(device="cpu").manual_seed(1)
+    k_new = torch.randn(T, L.n_kv_heads, L.head_dim, generator=g).to(torch.bfloat16)
+    v_new = torch.randn(T, L.n_kv_heads, L.head_dim, generator=g).to(torch.bfloat16)
+    mk = lambda n, fill: torch.full((n, L.n_kv_heads, L.head_dim), fill, dtype=torch.bfloat16, device=dev)
+    kp, vp, ks, vs = mk(b.n_prefix_kv, 1.0), mk(b.n_prefix_kv, 2.0), mk(b.n_suffix_kv, 3.0), mk(b.n_suffix_kv, 4.0)
+    bllm.kv_append(pg, k_new.to(dev), v_new.to(dev), kp, vp, ks, vs)
+    torch.cuda.synchronize()
+    want = {"kp": mk(b.n_prefix_kv, 1.0).cpu(), "vp": mk(b.n_prefix_kv, 2.0).cpu(), "ks": mk(b.n_suffix_kv, 3.0).cpu(),
+            "vs": mk(b.n_suffix_kv, 4.0).cpu()}
+    for t, d in enumerate(m["row_kv_dst"]):
+        if d >= 0:
+            want["ks"][d], want["vs"][d] = k_new[t], v_new[t]
+        else:
+            want["kp"][-d - 1], want["vp"][-d - 1] = k_new[t], v_new[t]
+    for got, name in ((kp, "kp"), (vp, "vp"), (ks, "ks"), (vs, "vs")):
+        assert torch.equal(got.cpu(), want[name]), name
+    with pytest.raises(bllm.BllmError):
+        bllm.kv_append(pg, k_new.to(dev), v_new.to(dev), None, vp, ks, vs)     # the batch has prefix rows
+    with pytest.raises(bllm.BllmError):
+        bllm.kv_append(pg, None, v_new.to(dev), kp, vp, ks, vs)
     pg.destroy()

@@ -267,9 +267,22 @@ def with_prefix_prefill(batch, seed=0, max_rows=None):
                  batch.req_q_len, seed=batch.seed, note=batch.note, prefix_q_len=pq)
 
 
+def l8b_decode_prefill(seed=0, shuffle=False):
+    """The decode batch of l8b_decode plus one new group whose 4096-token prefix gets its second
+    2048-row chunk in the same iteration (Sec. 3.3.1: decode tokens first, the rest of the token
+    budget goes to prefill chunks; the common-prefix queue feeds the batch too).  The new group has
+    no requests yet: a prefix is prefilled before its distinct prompts."""
+    d = l8b_decode(seed, shuffle)
+    pq = np.zeros(d.n_groups + 1, dtype=np.int32)
+    pq[-1] = 2048
+    return Batch("l8b_decode_prefill", d.layer, np.append(d.prefix_len, 4096).astype(np.int32), d.req_group,
+                 d.req_suffix_len, d.req_q_len, seed=seed, note=d.note, prefix_q_len=pq)
+
+
 CONFIGS = {
     "tiny_fp32": tiny_fp32,
     "l8b_decode": l8b_decode,
+    "l8b_decode_prefill": l8b_decode_prefill,
     "l8b_mixed": l8b_mixed,
     "l8b_mixed_full": lambda seed=0, shuffle=False: l8b_mixed(seed, shuffle, full=True),
     "rank_longprefix": rank_longprefix,
