@@ -302,6 +302,37 @@ def host_steps(batch, bllm, with_oracle=True):
         t0 = time.perf_counter()
         ref.identify_prefix_groups(sample)
         out["prefix_identification"]["oracle_ms_on_640_prompts"] = round((time.perf_counter() - t0) * 1e3, 1)
+    out["token_batching"] = token_batching_job(bllm, with_oracle)
+    return out
+
+
+def token_batching_job(bllm, with_oracle):
+    """The token batches of a whole synthetic job shaped like the paper's offline workloads (Sec. 4.2:
+    3000 requests, sharing degree about 3, prefix about 1.5k tokens, distinct part about 30, outputs in a
+    narrow range; Sec. 3.3.3: S_chunk tokens per batch): tokens per iteration with the paper's batching
+    (groups reordered by Eq. 3, limited by the KV memory) and with a request-count limit of 256 in arrival
+    order, the setting the paper contrasts it with."""
+    rng = np.random.default_rng(1)
+    n_groups = 1000
+    prefix_len = rng.integers(1200, 1900, n_groups)
+    req_group = np.repeat(np.arange(n_groups), 3)
+    distinct = rng.integers(10, 60, req_group.shape[0])
+    decode = rng.integers(96, 160, req_group.shape[0])
+    job = (prefix_len, req_group, distinct, decode)
+    out = {"input": "1000 groups x 3 requests, prefix U[1200,1900), distinct U[10,60), output U[96,160); "
+                    "S_chunk 2048, M_threshold 400000 KV tokens"}
+    for name, kw in (("memory_centric_reordered", {}), ("request_limit_256_arrival_order", {"max_requests": 256, "reorder": False})):
+        t0 = time.perf_counter()
+        tokens, kv = bllm.Job(*job, 2048, 400000, **kw).counts()
+        dt = time.perf_counter() - t0
+        out[name] = {"ms": round(dt * 1e3, 2), "iterations": int(len(tokens)), "mean_tokens_per_iteration": round(float(tokens.mean()), 1),
+                     "iterations_below_half_chunk": int((tokens < 1024).sum()), "peak_kv_tokens": int(kv.max())}
+    if with_oracle:
+        from oracle import token_batching as ref
+        sub = (prefix_len[:100], req_group[:300], distinct[:300], decode[:300])
+        t0 = time.perf_counter()
+        ref.run_job(*sub, 2048, 400000)
+        out["oracle_ms_on_300_requests"] = round((time.perf_counter() - t0) * 1e3, 1)
     return out
 
 

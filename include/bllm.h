@@ -253,6 +253,66 @@ int bllm_prefix_shared_attention(const bllm_prefix_groups* pg, const void* q,
                                  void* workspace, size_t workspace_bytes,
                                  void* o_out, float* lse_out, void* hip_stream);
 
+/* Throughput-oriented token batching on the host (Sec. 3.3): plays a job of
+ * prefix-sharing groups through, iteration by iteration, and hands out the token
+ * batch of every iteration in the form bllm_prefix_group_create_ex takes.
+ *  - Groups take their turn in the order of R_group = 1 / (L_prefix + sum
+ *    L_distinct), larger first (Eq. 3), ties by group index; reorder = 0 keeps the
+ *    order given.
+ *  - Every iteration fetches decode tokens (one per request in its decode phase,
+ *    in the order the requests entered it), then chunks of distinct prompts (queue
+ *    order: by group turn, user order inside a group), then chunks of common
+ *    prefixes (Sec. 3.3.1).  The requests of a group join the distinct-prompt queue
+ *    when the chunk that completes their prefix has been fetched, so they are
+ *    fetched from the next iteration on; a group with prefix length 0 joins when its
+ *    turn comes.
+ *  - A prefill chunk is min(what is left of it, what is left of s_chunk, what is
+ *    left of m_threshold); when the memory leaves nothing, no further prefill is
+ *    fetched in the iteration (Sec. 3.3.3).  Decode tokens count against s_chunk
+ *    only.  max_requests > 0 adds a request-count limit per batch (a prefix chunk
+ *    counts as one); 0 = none, the paper's setting.
+ *  - KV memory in use, in tokens: a group's prefix once, from its first chunk until
+ *    its last request finishes, plus every unfinished request's own tokens.
+ *  - The iteration that completes a request's prompt yields its first output
+ *    token: a request with decode_len output tokens has decode_len - 1 decode
+ *    iterations. */
+typedef struct {
+    int32_t s_chunk;        /* tokens per batch, >= 1 */
+    int32_t max_requests;   /* 0: no request-count limit */
+    int32_t reorder;        /* non-zero: groups in the order of Eq. 3 */
+    int32_t reserved;       /* 0 */
+    int64_t m_threshold;    /* KV tokens, >= 1 */
+} bllm_batching_params;
+
+/* One iteration's token batch; the arrays belong to the job and are valid until
+ * the next call on it.  groups / requests are user ids, ascending; prefix_len,
+ * prefix_q_len, req_group (index into groups), req_suffix_len, req_q_len are the
+ * arguments of bllm_prefix_group_create_ex (lengths include this batch's rows). */
+typedef struct {
+    int32_t iteration;
+    int32_t n_groups;    const int32_t* groups; const int32_t* prefix_len; const int32_t* prefix_q_len;
+    int32_t n_requests;  const int32_t* requests; const int32_t* req_group;
+    const int32_t* req_suffix_len; const int32_t* req_q_len;
+    int32_t n_decode_tokens, n_distinct_tokens, n_prefix_tokens;
+    int64_t kv_in_use;   /* after this batch's tokens were added, before the releases at its end */
+} bllm_token_batch;
+
+typedef struct bllm_job bllm_job;   /* opaque */
+
+/* All arrays host, copied.  req_distinct_len >= 0, req_decode_len >= 1, every
+ * request has at least one prompt token (prefix or distinct).  Errors: INVALID_ARG,
+ * OUT_OF_MEMORY. */
+int bllm_job_create(const bllm_batching_params* params,
+                    int32_t n_groups, const int32_t* prefix_len,
+                    int32_t n_requests, const int32_t* req_group,
+                    const int32_t* req_distinct_len, const int32_t* req_decode_len,
+                    bllm_job** out);
+/* Next iteration.  *done = 1 (and an empty batch) once every request has finished.
+ * BLLM_UNSUPPORTED when an iteration can schedule nothing although work is left:
+ * m_threshold is too small for the job (the job stays where it was). */
+int bllm_job_next_batch(bllm_job* job, bllm_token_batch* out, int32_t* done);
+int bllm_job_destroy(bllm_job* job);
+
 /* Global prefix identification on the host (Sec. 3.2): builds the compact prefix
  * tree of the prompts, enlarges the first-level prefixes with the fork-and-merge
  * pass of Alg. 1 (fork a first-level node and merge it with one of its children when

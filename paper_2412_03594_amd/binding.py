@@ -16,7 +16,7 @@ EXPORTS = ["bllm_prefix_group_create", "bllm_prefix_group_create_host", "bllm_pr
            "bllm_prefix_group_destroy", "bllm_shared_prefix_attention", "bllm_suffix_attention", "bllm_lse_merge",
            "bllm_suffix_attention_merged", "bllm_prefix_shared_attention", "bllm_prefix_shared_workspace_bytes",
            "bllm_identify_prefix_groups", "bllm_last_error", "bllm_version", "bllm_prefix_group_create_ex",
-           "bllm_kv_append"]
+           "bllm_kv_append", "bllm_job_create", "bllm_job_next_batch", "bllm_job_destroy"]
 
 
 class BllmError(RuntimeError):
@@ -48,6 +48,20 @@ class PackingView(C.Structure):
                 ("prefix_row_split", _I32P), ("suffix_row_split", _I32P)]
 
 
+class BatchingParams(C.Structure):
+    _fields_ = [("s_chunk", C.c_int32), ("max_requests", C.c_int32), ("reorder", C.c_int32), ("reserved", C.c_int32),
+                ("m_threshold", C.c_int64)]
+
+
+class TokenBatch(C.Structure):
+    _fields_ = [("iteration", C.c_int32),
+                ("n_groups", C.c_int32), ("groups", _I32P), ("prefix_len", _I32P), ("prefix_q_len", _I32P),
+                ("n_requests", C.c_int32), ("requests", _I32P), ("req_group", _I32P), ("req_suffix_len", _I32P),
+                ("req_q_len", _I32P),
+                ("n_decode_tokens", C.c_int32), ("n_distinct_tokens", C.c_int32), ("n_prefix_tokens", C.c_int32),
+                ("kv_in_use", C.c_int64)]
+
+
 def lib_path():
     return os.path.join(_HERE, "libbllm.so")
 
@@ -72,6 +86,12 @@ def load_library():
     lib.bllm_prefix_group_create_ex.restype = C.c_int
     lib.bllm_kv_append.argtypes = [h] + [C.c_void_p] * 7
     lib.bllm_kv_append.restype = C.c_int
+    lib.bllm_job_create.argtypes = [C.POINTER(BatchingParams), C.c_int32, _I32P, C.c_int32, _I32P, _I32P, _I32P,
+                                    C.POINTER(h)]
+    lib.bllm_job_next_batch.argtypes = [h, C.POINTER(TokenBatch), C.POINTER(C.c_int32)]
+    lib.bllm_job_destroy.argtypes = [h]
+    for name in ("bllm_job_create", "bllm_job_next_batch", "bllm_job_destroy"):
+        getattr(lib, name).restype = C.c_int
     lib.bllm_prefix_group_metadata.argtypes = [h, C.POINTER(PackingView)]
     lib.bllm_prefix_group_destroy.argtypes = [h]
     for name in ("bllm_shared_prefix_attention", "bllm_suffix_attention"):
@@ -232,6 +252,62 @@ def kv_append(pg, k_new, v_new, k_prefix, v_prefix, k_suffix, v_suffix, stream=N
 def lse_merge(pg, o_a, lse_a, o_b, lse_b, o_out, lse_out=None, stream=None):
     _check(load_library().bllm_lse_merge(pg.handle, _ptr(o_a), _ptr(lse_a), _ptr(o_b), _ptr(lse_b), _ptr(o_out),
                                          _ptr(lse_out), _stream(stream)))
+
+
+class Job:
+    """Owns a bllm_job: the token batches of a whole job, one per call of next_batch()."""
+
+    def __init__(self, prefix_len, req_group, req_distinct_len, req_decode_len, s_chunk, m_threshold, max_requests=0,
+                 reorder=True):
+        lib = load_library()
+        pl, plp = _i32(prefix_len)
+        rg, rgp = _i32(req_group)
+        rd, rdp = _i32(req_distinct_len)
+        rn, rnp = _i32(req_decode_len)
+        if not (len(rg) == len(rd) == len(rn)):
+            raise ValueError("request arrays differ in length")
+        params = BatchingParams(int(s_chunk), int(max_requests), 1 if reorder else 0, 0, int(m_threshold))
+        self._h = C.c_void_p()
+        _check(lib.bllm_job_create(C.byref(params), len(pl), plp, len(rg), rgp, rdp, rnp, C.byref(self._h)))
+
+    def next_batch(self):
+        """The next iteration's batch as a dict of lists / ints (copies), or None when the job is done."""
+        b, done = TokenBatch(), C.c_int32(0)
+        _check(load_library().bllm_job_next_batch(self._h, C.byref(b), C.byref(done)))
+        if done.value:
+            return None
+        arr = lambda p, n: [int(p[i]) for i in range(n)]
+        g, r = b.n_groups, b.n_requests
+        return {"iteration": b.iteration, "groups": arr(b.groups, g), "prefix_len": arr(b.prefix_len, g),
+                "prefix_q_len": arr(b.prefix_q_len, g), "requests": arr(b.requests, r), "req_group": arr(b.req_group, r),
+                "req_suffix_len": arr(b.req_suffix_len, r), "req_q_len": arr(b.req_q_len, r),
+                "n_decode_tokens": b.n_decode_tokens, "n_distinct_tokens": b.n_distinct_tokens,
+                "n_prefix_tokens": b.n_prefix_tokens, "kv_in_use": int(b.kv_in_use)}
+
+    def counts(self):
+        """Plays the rest of the job; returns (tokens per iteration, KV tokens in use per iteration) as arrays
+        without copying the batches."""
+        lib = load_library()
+        b, done = TokenBatch(), C.c_int32(0)
+        tokens, kv = [], []
+        while True:
+            _check(lib.bllm_job_next_batch(self._h, C.byref(b), C.byref(done)))
+            if done.value:
+                break
+            tokens.append(b.n_decode_tokens + b.n_distinct_tokens + b.n_prefix_tokens)
+            kv.append(b.kv_in_use)
+        return np.asarray(tokens, dtype=np.int64), np.asarray(kv, dtype=np.int64)
+
+    def destroy(self):
+        if self._h is not None:
+            h, self._h = self._h, None
+            _check(load_library().bllm_job_destroy(h))
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
 
 
 def identify_prefix_groups_flat(prompt_start, tokens):
