@@ -209,7 +209,15 @@ def run_workload(name, steps, warmup, seed, rotate, torch, bllm, workload, with_
         b = nxt()
         bllm.prefix_shared_attention(pg, q, b[0], b[1], b[2], b[3], ws, o, None)
 
-    step = {"one_call": step_one_call, "fused": step_fused, "three_call": step_three_call}[schedule]
+    single_ok = L.dtype == workload.BF16 and L.head_dim == 128
+    ws2 = torch.empty(bllm.prefix_shared_single_launch_workspace_bytes(pg) // 4 + 1, device=dev, dtype=torch.float32)
+
+    def step_single_launch():
+        b = nxt()
+        bllm.prefix_shared_attention_single_launch(pg, q, b[0], b[1], b[2], b[3], ws2, o, None)
+
+    step = {"one_call": step_one_call, "fused": step_fused, "three_call": step_three_call,
+            "single_launch": step_single_launch}[schedule]
 
     # One captured HIP graph per KV copy: a replay is exactly one step; the launches of a step reach
     # the GPU as one submission, without per-kernel launch gaps.
@@ -253,9 +261,13 @@ def run_workload(name, steps, warmup, seed, rotate, torch, bllm, workload, with_
               "suffix_merged": time_loop(suffix_merged_pass, steps, warmup, torch),
               "one_call": time_loop(step_one_call, steps, warmup, torch),
               "kv_append": time_loop(kv_append_pass, steps, warmup, torch)}
+    if single_ok:
+        t_pass["single_launch"] = time_loop(step_single_launch, steps, warmup, torch)
     work = algorithmic_work(batch, meta)
     passes = {}
-    for k in ("prefix", "suffix", "merge", "suffix_merged", "one_call", "kv_append"):
+    work["single_launch"] = {"bytes": work["prefix"]["bytes"] + work["suffix"]["bytes"] + work["merge"]["bytes"],
+                             "flops": work["one_call"]["flops"]}
+    for k in t_pass:
         sec = t_pass[k] * 1e-3
         passes[k] = {"ms": round(t_pass[k], 5), "GB_s": round(work[k]["bytes"] / sec / 1e9, 1),
                      "TFLOP_s": round(work[k]["flops"] / sec / 1e12, 2),
@@ -339,21 +351,25 @@ def token_batching_job(bllm, with_oracle):
 def roofline_of(res):
     """Roofline record of the pass that takes the most time."""
     t = res["t_pass"]
-    in_step = ("prefix", "suffix", "merge") if res["schedule"] == "three_call" else ("prefix", "suffix_merged")
+    in_step = {"three_call": ("prefix", "suffix", "merge"), "single_launch": ("single_launch",)}.get(
+        res["schedule"], ("prefix", "suffix_merged"))
     name = max(in_step, key=lambda k: t[k])
     traffic = MEASURED_TRAFFIC_BYTES.get(res["batch"].name, {}).get(name)
     w = res["work"][name]
     sec = t[name] * 1e-3
     # arithmetic intensity decides which roof bounds the pass
     ai = w["flops"] / max(w["bytes"], 1.0)
-    if name == "prefix" and ai > PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9):
+    if name in ("prefix", "single_launch") and ai > PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9):
         a = w["flops"] / sec / 1e12
-        return {"kernel": "tile_attention_kernel (shared-prefix pass)", "bound": "mfma", "achieved": round(a, 2),
+        return {"kernel": "tile_attention_kernel (shared-prefix pass)" if name == "prefix" else
+                "hfused_attention_kernel (prefix tiles, chunk tiles and streaming items in one launch)",
+                "bound": "mfma", "achieved": round(a, 2),
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(a / PEAK_BF16_TFLOPS, 4), "traffic": traffic}
     a = w["bytes"] / sec / 1e9
     kern = {"prefix": "tile_attention_kernel (shared-prefix pass)",
             "suffix": "stream_attention_kernel (distinct-suffix pass)", "merge": "lse_merge_kernel",
-            "suffix_merged": "stream_attention_kernel (distinct-suffix pass, reduction in the epilogue)"}[name]
+            "suffix_merged": "stream_attention_kernel (distinct-suffix pass, reduction in the epilogue)",
+            "single_launch": "hfused_attention_kernel (prefix tiles, chunk tiles and streaming items in one launch)"}[name]
     return {"kernel": kern, "bound": "hbm", "achieved": round(a, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
             "frac": round(a / PEAK_HBM_GBS, 4), "traffic": traffic}
 
@@ -369,11 +385,12 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--rotate", type=int, default=0,
                     help="copies of the KV tensors cycled through (0: enough to defeat the Infinity Cache, 2..16)")
-    ap.add_argument("--schedule", choices=["fused", "one_call", "three_call"], default="fused",
+    ap.add_argument("--schedule", choices=["fused", "one_call", "three_call", "single_launch"], default="fused",
                     help="timed step: prefix pass + suffix pass with the reduction in its epilogue (two calls); the "
                          "one-call entry point (prefix kernels, then suffix kernels that fold the prefix result - split "
                          "pieces included - in their epilogue); or prefix, suffix and merge passes (three calls).  "
-                         "All give the same final output")
+                         "single_launch: every part a workgroup of one kernel, the last part to arrive at a row reduces "
+                         "it (bf16, head_dim 128).  All give the same final output")
     ap.add_argument("--graph", action="store_true",
                     help="replay one captured HIP graph per timed step instead of launching eagerly (measured slower "
                          "than eager launches on the decode workload, faster on the long-running ones)")

@@ -216,6 +216,26 @@ int bllm_suffix_attention_merged(const bllm_prefix_groups* pg, const void* q,
                                  const float* o_prefix, const float* lse_prefix,
                                  void* o_out, float* lse_out, void* hip_stream);
 
+/* The whole path as ONE launch (Sec. 4.3.3: horizontal fusion - the partial
+ * attention on the shared prefix and on the distinct part run as different
+ * thread blocks of one kernel, each with its own tiling; Sec. 5: reduced through
+ * online softmax).  Every part writes its fp32 partial result into the workspace
+ * and arrives at a counter of each (token row, KV head) it covered; the part that
+ * arrives last reduces that row's partials and writes the final output.  No part
+ * waits for another.  The result equals the other call sequences up to fp32
+ * rounding.  bf16 with head_dim 128 only (BLLM_UNSUPPORTED otherwise: use
+ * bllm_prefix_shared_attention).
+ *   arguments as bllm_prefix_shared_attention; the workspace must hold
+ *   bllm_prefix_shared_single_launch_workspace_bytes(pg) bytes.
+ * The arrival counters belong to the handle (zero between calls): calls on one
+ * handle must not overlap, on whatever streams.  Allocates nothing. */
+size_t bllm_prefix_shared_single_launch_workspace_bytes(const bllm_prefix_groups* pg);
+int bllm_prefix_shared_attention_single_launch(const bllm_prefix_groups* pg, const void* q,
+                                               const void* k_prefix, const void* v_prefix,
+                                               const void* k_suffix, const void* v_suffix,
+                                               void* workspace, size_t workspace_bytes,
+                                               void* o_out, float* lse_out, void* hip_stream);
+
 /* Write the new keys and values of the batch's own tokens into the KV memory,
  * which keeps every shared prefix once per group apart from the distinct parts
  * of the requests (Sec. 3.3.1, Sec. 3.4): packed row t goes to row row_kv_dst[t]

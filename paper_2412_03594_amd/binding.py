@@ -16,7 +16,8 @@ EXPORTS = ["bllm_prefix_group_create", "bllm_prefix_group_create_host", "bllm_pr
            "bllm_prefix_group_destroy", "bllm_shared_prefix_attention", "bllm_suffix_attention", "bllm_lse_merge",
            "bllm_suffix_attention_merged", "bllm_prefix_shared_attention", "bllm_prefix_shared_workspace_bytes",
            "bllm_identify_prefix_groups", "bllm_last_error", "bllm_version", "bllm_prefix_group_create_ex",
-           "bllm_kv_append", "bllm_job_create", "bllm_job_next_batch", "bllm_job_destroy"]
+           "bllm_kv_append", "bllm_job_create", "bllm_job_next_batch", "bllm_job_destroy",
+           "bllm_prefix_shared_attention_single_launch", "bllm_prefix_shared_single_launch_workspace_bytes"]
 
 
 class BllmError(RuntimeError):
@@ -102,6 +103,10 @@ def load_library():
                                                  C.c_void_p, C.c_void_p, C.c_void_p]
     lib.bllm_prefix_shared_attention.argtypes = [h, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                                  C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.bllm_prefix_shared_attention_single_launch.argtypes = lib.bllm_prefix_shared_attention.argtypes
+    lib.bllm_prefix_shared_attention_single_launch.restype = C.c_int
+    lib.bllm_prefix_shared_single_launch_workspace_bytes.argtypes = [h]
+    lib.bllm_prefix_shared_single_launch_workspace_bytes.restype = C.c_size_t
     lib.bllm_prefix_shared_workspace_bytes.argtypes = [h]
     lib.bllm_prefix_shared_workspace_bytes.restype = C.c_size_t
     for name in EXPORTS[:9]:
@@ -242,6 +247,19 @@ def suffix_attention(pg, q, k_suffix, v_suffix, o_part, lse_part, stream=None):
 def suffix_attention_merged(pg, q, k_suffix, v_suffix, o_prefix, lse_prefix, o_out, lse_out=None, stream=None):
     _check(load_library().bllm_suffix_attention_merged(pg.handle, _ptr(q), _ptr(k_suffix), _ptr(v_suffix), _ptr(o_prefix),
                                                        _ptr(lse_prefix), _ptr(o_out), _ptr(lse_out), _stream(stream)))
+
+
+def prefix_shared_single_launch_workspace_bytes(pg):
+    return int(load_library().bllm_prefix_shared_single_launch_workspace_bytes(pg.handle))
+
+
+def prefix_shared_attention_single_launch(pg, q, k_prefix, v_prefix, k_suffix, v_suffix, workspace, o_out, lse_out=None,
+                                          stream=None):
+    """workspace: a device tensor of at least prefix_shared_single_launch_workspace_bytes(pg) bytes."""
+    nbytes = workspace.numel() * workspace.element_size()
+    _check(load_library().bllm_prefix_shared_attention_single_launch(
+        pg.handle, _ptr(q), _ptr(k_prefix), _ptr(v_prefix), _ptr(k_suffix), _ptr(v_suffix), _ptr(workspace), nbytes,
+        _ptr(o_out), _ptr(lse_out), _stream(stream)))
 
 
 def kv_append(pg, k_new, v_new, k_prefix, v_prefix, k_suffix, v_suffix, stream=None):

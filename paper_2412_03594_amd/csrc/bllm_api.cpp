@@ -92,10 +92,11 @@ int upload(bllm_prefix_groups* pg, hipStream_t stream) {
     if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
     const size_t row_elems = static_cast<size_t>(pg->desc.n_q_heads) * pg->desc.head_dim;
     const size_t ws_rows = static_cast<size_t>(std::max(p.n_prefix_ws_rows, p.n_suffix_ws_rows));
-    const size_t sizes[9] = {bytes_of(p.prefix_tile_items), bytes_of(p.prefix_row_items), bytes_of(p.suffix_tile_items),
+    const size_t sizes[10] = {bytes_of(p.prefix_tile_items), bytes_of(p.prefix_row_items), bytes_of(p.suffix_tile_items),
                              bytes_of(p.suffix_row_items),  bytes_of(p.prefix_row_split), bytes_of(p.suffix_row_split),
                              align256(ws_rows * row_elems * sizeof(float)),
-                             align256(ws_rows * pg->desc.n_q_heads * sizeof(float)), bytes_of(p.row_kv_dst)};
+                             align256(ws_rows * pg->desc.n_q_heads * sizeof(float)), bytes_of(p.row_kv_dst),
+                             align256(static_cast<size_t>(p.n_rows) * pg->desc.n_kv_heads * sizeof(int32_t))};
     size_t total = 256;
     for (size_t s : sizes) total += s;
     e = hipMalloc(&pg->dev_blob, total);
@@ -116,6 +117,9 @@ int upload(bllm_prefix_groups* pg, hipStream_t stream) {
     pg->d.ws_o = reinterpret_cast<float*>(place(sizes[6]));
     pg->d.ws_lse = reinterpret_cast<float*>(place(sizes[7]));
     pg->d.row_kv_dst = reinterpret_cast<int32_t*>(place(sizes[8]));
+    pg->d.arrivals = reinterpret_cast<int32_t*>(place(sizes[9]));
+    e = hipMemsetAsync(pg->d.arrivals, 0, sizes[9], stream);      // at create only; the kernels keep them at zero
+    if (e != hipSuccess) return hip_fail(e, "hipMemsetAsync(arrival counters)");
 
     auto copy = [&](void* dst, const void* src, size_t n) -> hipError_t {
         if (n == 0) return hipSuccess;
@@ -407,6 +411,58 @@ int bllm_prefix_shared_attention(const bllm_prefix_groups* pg, const void* q, co
         mt.ws_lse = pg->d.ws_lse;
     }
     return launch_pass_kernels(pg, false, q, k_suffix, v_suffix, nullptr, nullptr, mt, hip_stream);
+}
+
+size_t bllm_prefix_shared_single_launch_workspace_bytes(const bllm_prefix_groups* pg) {
+    return 2 * bllm_prefix_shared_workspace_bytes(pg);
+}
+
+int bllm_prefix_shared_attention_single_launch(const bllm_prefix_groups* pg, const void* q, const void* k_prefix,
+                                               const void* v_prefix, const void* k_suffix, const void* v_suffix,
+                                               void* workspace, size_t workspace_bytes, void* o_out, float* lse_out,
+                                               void* hip_stream) {
+    int rc = check_device_call(pg, {q, workspace, o_out});
+    if (rc != BLLM_OK) return rc;
+    const Packing& p = pg->pk;
+    if (pg->desc.dtype != BLLM_BF16 || pg->desc.head_dim != 128) {
+        set_error("the single-launch path covers bf16 with head_dim 128 only");
+        return BLLM_UNSUPPORTED;
+    }
+    if (p.n_rows == 0) return BLLM_OK;
+    if (workspace_bytes < bllm_prefix_shared_single_launch_workspace_bytes(pg) ||
+        (reinterpret_cast<uintptr_t>(workspace) & 15) != 0) {
+        set_error("workspace too small (see bllm_prefix_shared_single_launch_workspace_bytes) or not 16-byte aligned");
+        return BLLM_INVALID_ARG;
+    }
+    if ((p.prefix_kv_start.back() > 0 && (!k_prefix || !v_prefix)) || (p.req_kv_start.back() > 0 && (!k_suffix || !v_suffix))) {
+        set_error("null KV pointer");
+        return BLLM_INVALID_ARG;
+    }
+    // [prefix partial O | L | suffix partial O | L], each as in bllm_prefix_shared_attention
+    const size_t row_heads = static_cast<size_t>(p.n_rows) * pg->desc.n_q_heads;
+    const size_t o_bytes = align256(row_heads * pg->desc.head_dim * sizeof(float));
+    const size_t l_bytes = align256(row_heads * sizeof(float));
+    char* w = static_cast<char*>(workspace);
+    float* o1 = reinterpret_cast<float*>(w);
+    float* l1 = reinterpret_cast<float*>(w + o_bytes);
+    float* o2 = reinterpret_cast<float*>(w + o_bytes + l_bytes);
+    float* l2 = reinterpret_cast<float*>(w + 2 * o_bytes + l_bytes);
+    HFusedLists lists;
+    lists.prefix_tiles = pg->d.prefix_tile_items;
+    lists.suffix_tiles = pg->d.suffix_tile_items;
+    lists.suffix_rows = pg->d.suffix_row_items;
+    lists.n_prefix_tiles = static_cast<int32_t>(p.prefix_tile_items.size());
+    lists.n_suffix_tiles = static_cast<int32_t>(p.suffix_tile_items.size());
+    lists.n_suffix_rows = static_cast<int32_t>(p.suffix_row_items.size());
+    lists.n_request_rows = p.group_prefix_row_start[0];
+    lists.prefix_row_split = pg->d.prefix_row_split;
+    lists.ws_o = pg->d.ws_o;
+    lists.ws_lse = pg->d.ws_lse;
+    lists.arrivals = pg->d.arrivals;
+    const hipError_t e = launch_hfused_attention(make_ctx(pg, hip_stream), lists, p.suffix_stream_wpi, q, k_prefix, v_prefix,
+                                                 k_suffix, v_suffix, o1, l1, o2, l2, o_out, lse_out);
+    if (e != hipSuccess) return hip_fail(e, "single-launch attention");
+    return BLLM_OK;
 }
 
 const char* bllm_last_error(void) { return g_last_error.c_str(); }

@@ -80,6 +80,54 @@ __device__ __forceinline__ float fold_result(const PartialFold& f, float4& o) {
     return f.den > 0.f ? f.top + logf(f.den) : -INFINITY;
 }
 
+// Partial results that another workgroup of the SAME launch will read (single-launch path) are written
+// and read with device-scope coherent accesses (the cache-policy bit the compiler gives a device-scope
+// atomic access): such a store goes through to the level all compute dies share, such a load does not
+// hit a stale line of the reader's own L2, and neither needs the whole-L2 write-back / invalidate of a
+// device-scope fence.  Single words are atomic accesses; 16-byte accesses, for which there is no atomic
+// form, are written as the same instruction with the same bit.  The compiler does not count those, so
+// coherent_stores_done() / the wait inside load_coherent_pair() wait for them explicitly.
+typedef float float4r __attribute__((ext_vector_type(4)));
+template <bool kCoherent>
+__device__ __forceinline__ void store_partial1(float* p, float x) {
+    if constexpr (kCoherent) __hip_atomic_store(p, x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else *p = x;
+}
+template <bool kCoherent>
+__device__ __forceinline__ void store_partial4(float* p, float x0, float x1, float x2, float x3) {
+    if constexpr (kCoherent) {
+#if defined(__HIP_DEVICE_COMPILE__)
+        const float4r v = {x0, x1, x2, x3};
+        // the two idle cycles keep a following vector instruction from overwriting the data registers while
+        // the store still reads them (the compiler inserts them itself for stores it knows about)
+        asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" : : "v"(p), "v"(v) : "memory");
+#endif
+    } else {
+        *reinterpret_cast<float4*>(p) = make_float4(x0, x1, x2, x3);
+    }
+}
+// every coherent 16-byte store of this wavefront has completed
+__device__ __forceinline__ void coherent_stores_done() {
+#if defined(__HIP_DEVICE_COMPILE__)
+    asm volatile("s_waitcnt vmcnt(0)" : : : "memory");
+#endif
+}
+__device__ __forceinline__ float load_coherent1(const float* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// two coherent 16-byte loads in flight together, then the wait; the results are tied to the wait
+__device__ __forceinline__ void load_coherent_pair(const float* pa, const float* pb, float4& a, float4& b) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    float4r va, vb;
+    asm volatile("global_load_dwordx4 %0, %2, off sc1\n\tglobal_load_dwordx4 %1, %3, off sc1\n\ts_waitcnt vmcnt(0)"
+                 : "=&v"(va), "=&v"(vb)
+                 : "v"(pa), "v"(pb)
+                 : "memory");
+    a = make_float4(va[0], va[1], va[2], va[3]);
+    b = make_float4(vb[0], vb[1], vb[2], vb[3]);
+#endif
+}
+
 // Stores 4 consecutive merged elements at element offset `off` of an output in the layer's dtype.
 template <bool kBf16Out>
 __device__ __forceinline__ void store_out4(void* out, size_t off, float x0, float x1, float x2, float x3) {

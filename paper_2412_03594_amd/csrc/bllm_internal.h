@@ -55,6 +55,7 @@ struct DeviceLists {
     RowSplit* prefix_row_split = nullptr;
     RowSplit* suffix_row_split = nullptr;
     int32_t* row_kv_dst = nullptr;
+    int32_t* arrivals = nullptr;   // [n_rows, Hkv] arrival counters of the single-launch path, zero between calls
     float* ws_o = nullptr;     // [ws_rows, Hq, D]
     float* ws_lse = nullptr;   // [ws_rows, Hq]
 };
@@ -112,6 +113,21 @@ hipError_t launch_tile_attention(const LaunchCtx& c, const Item* items, int32_t 
                                  float* ws_lse, const MergeTarget& mt);
 hipError_t launch_split_combine(const LaunchCtx& c, const RowSplit* row_split, const float* ws_o, const float* ws_lse,
                                 float* o_part, float* lse_part);
+// The whole path as one launch (bf16, head_dim 128 only): prefix tiles, chunk tiles and streaming items as
+// workgroups of one grid; the last part to arrive at a (row, KV head) reduces its partials.
+struct HFusedLists {
+    const Item* prefix_tiles;
+    const Item* suffix_tiles;
+    const Item* suffix_rows;
+    int32_t n_prefix_tiles, n_suffix_tiles, n_suffix_rows, n_request_rows;
+    const RowSplit* prefix_row_split;
+    float* ws_o;
+    float* ws_lse;
+    int32_t* arrivals;
+};
+hipError_t launch_hfused_attention(const LaunchCtx& c, const HFusedLists& lists, int suffix_wpi, const void* q,
+                                   const void* k_prefix, const void* v_prefix, const void* k_suffix, const void* v_suffix,
+                                   float* o1, float* l1, float* o2, float* l2, void* o_out, float* lse_out);
 // Copies row t of k_new / v_new ([n_rows, Hkv, D], layer dtype) to row row_kv_dst[t] of the suffix arrays,
 // or row -row_kv_dst[t] - 1 of the prefix arrays when negative.
 hipError_t launch_kv_append(const LaunchCtx& c, const int32_t* row_kv_dst, const void* k_new, const void* v_new,

@@ -1,0 +1,213 @@
+// Horizontally fused prefix-shared attention (BatchLLM Sec. 4.3.3: the partial attention on the
+// shared prefix and on the distinct part run as different thread blocks of ONE launch, each with
+// its own tiling, which removes the tail of one kernel before the next and the launch gaps).
+//
+// Workgroup b of the grid takes, in this order, a matrix-core tile of the shared-prefix part, a
+// matrix-core tile of a prefill chunk of the distinct part, or 4 / WPI streaming items (decode
+// rows).  Every part writes its fp32 partial result to the workspace exactly as the separate
+// passes do; then it ARRIVES at the counter of each (token row, KV head) it covered.  The part
+// that arrives last at a counter reduces all partials of that row and head through online
+// softmax and writes the final output (Sec. 5).  Nobody waits for anybody: there is no spinning,
+// every workgroup runs to its end whatever the others do.
+//
+// Ordering: the partial results are written with device-scope atomic stores (they go through to
+// the level all compute dies share); the barrier of the workgroup waits until every wavefront's
+// stores have completed, and only then does one thread per (row, KV head) increment the counter
+// with a device-scope atomic.  The workgroup that sees the last count reads the other parts'
+// partials with device-scope atomic loads, after the count.  A device-scope FENCE is avoided on
+// purpose: it writes back and invalidates a whole L2, and with thousands of workgroups doing so the
+// launch measured 8 times slower than the separate passes.  The last arrival also puts the counter
+// back to zero for the next call.
+#include "stream_attention_body.h"
+#include "tile_attention_body.h"
+
+namespace bllm {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kMaxUnits = 128;        // token rows of a tile (32 * 4 wavefronts / rho) at rho = 1
+
+struct HFusedArgs {
+    const Item* prefix_tiles;
+    const Item* suffix_tiles;
+    const Item* suffix_rows;
+    int n_prefix_tiles, n_suffix_tiles, n_suffix_rows;
+    const uint16_t* q;
+    const uint16_t* k_prefix;
+    const uint16_t* v_prefix;
+    const uint16_t* k_suffix;
+    const uint16_t* v_suffix;
+    float* o1;            // prefix partial [T, Hq, D] (rows whose prefix is not split)
+    float* l1;            // [T, Hq]
+    float* o2;            // suffix partial
+    float* l2;
+    float* ws_o;          // pieces of split prefixes
+    float* ws_lse;
+    const RowSplit* prefix_row_split;    // [T]
+    int32_t* arrivals;    // [T, Hkv], zero before and after the launch
+    void* o_out;          // [T, Hq, D] bf16
+    float* lse_out;       // [T, Hq] or null
+    int n_q_heads, n_kv_heads, log2_rho, n_request_rows;
+    float scale;
+};
+
+template <int RHO, int WPI>
+__global__ __launch_bounds__(kThreads, RHO == 8 ? 1 : 2) void hfused_attention_kernel(HFusedArgs a) {
+    constexpr int kD = 128;
+    constexpr int kItemsPerBlock = 4 / WPI;
+    __shared__ int s_late_row[kMaxUnits];
+    __shared__ int s_late_head[kMaxUnits];
+    __shared__ int s_n_late;
+    const int tid = threadIdx.x;
+    const int b = blockIdx.x;
+    if (tid == 0) s_n_late = 0;
+
+    // ---- this workgroup's part --------------------------------------------------------------
+    int n_units;                 // (token row, KV head) pairs this workgroup produced a partial for
+    int unit_row = 0, unit_head = 0;     // the pair of thread tid, for tid < n_units
+    const MergeTarget none{};
+    if (b < a.n_prefix_tiles + a.n_suffix_tiles) {
+        const bool prefix = b < a.n_prefix_tiles;
+        const Item it = prefix ? a.prefix_tiles[b] : a.suffix_tiles[b - a.n_prefix_tiles];
+        tile_detail::tile_attention_body<4, 64, true>(it, a.q, prefix ? a.k_prefix : a.k_suffix, prefix ? a.v_prefix : a.v_suffix,
+                                                prefix ? a.o1 : a.o2, prefix ? a.l1 : a.l2, a.ws_o, a.ws_lse, a.n_q_heads,
+                                                a.n_kv_heads, a.log2_rho, a.scale, none);
+        n_units = it.n_rows;
+        unit_row = it.q_row0 + tid;
+        unit_head = it.kv_head;
+    } else {
+        const int sb = b - a.n_prefix_tiles - a.n_suffix_tiles;
+        stream_detail::stream_attention_body<true, kD, RHO, WPI, false, true>(sb, a.suffix_rows, a.n_suffix_rows, a.q, a.k_suffix,
+                                                                        a.v_suffix, a.o2, a.l2, a.ws_o, a.ws_lse, a.n_q_heads,
+                                                                        a.n_kv_heads, a.scale, none);
+        const int first = sb * kItemsPerBlock;
+        n_units = min(kItemsPerBlock, a.n_suffix_rows - first);
+        if (tid < n_units) {
+            const Item it = a.suffix_rows[first + tid];
+            unit_row = it.q_row0;
+            unit_head = it.kv_head;
+        }
+    }
+
+    // ---- arrive; the last arrival of a (row, KV head) reduces its partials ---------------------
+    coherent_stores_done();
+    __syncthreads();             // every wavefront's partial stores have completed
+    if (tid < n_units) {
+        const RowSplit sp = a.prefix_row_split[unit_row];
+        const int expected = (sp.n_splits > 0 ? sp.n_splits : 1) + (unit_row < a.n_request_rows ? 1 : 0);
+        int32_t* counter = a.arrivals + static_cast<size_t>(unit_row) * a.n_kv_heads + unit_head;
+        if (atomicAdd(counter, 1) == expected - 1) {
+            atomicExch(counter, 0);                       // every part has arrived: ready for the next call
+            const int slot = atomicAdd(&s_n_late, 1);
+            s_late_row[slot] = unit_row;
+            s_late_head[slot] = unit_head;
+        }
+    }
+    __syncthreads();
+    const int n_late = s_n_late;
+    if (n_late == 0) return;
+    constexpr int kPairs = RHO * (kD / 4);                // (head of the KV head, 4 consecutive elements)
+    for (int idx = tid; idx < n_late * kPairs; idx += kThreads) {
+        const int u = idx / kPairs;
+        const int p = idx - u * kPairs;
+        const int row = s_late_row[u];
+        const int head = s_late_head[u] * RHO + p / (kD / 4);
+        const int x = 4 * (p % (kD / 4));
+        const size_t rh = static_cast<size_t>(row) * a.n_q_heads + head;
+        // the partials of this element, two at a time: prefix pieces (or the one prefix partial), then
+        // the suffix partial; an absent one repeats the previous address and is not folded
+        PartialFold f;
+        const RowSplit sp = a.prefix_row_split[row];
+        const int n_prefix = sp.n_splits > 0 ? sp.n_splits : 1;
+        const int n_parts = n_prefix + (row < a.n_request_rows ? 1 : 0);
+        auto part = [&](int c, const float*& po, const float*& pl) {
+            if (c >= n_prefix) {
+                po = a.o2 + rh * kD + x;
+                pl = a.l2 + rh;
+            } else if (sp.n_splits > 0) {
+                const size_t wrh = static_cast<size_t>(sp.ws_row0 + c * sp.stride) * a.n_q_heads + head;
+                po = a.ws_o + wrh * kD + x;
+                pl = a.ws_lse + wrh;
+            } else {
+                po = a.o1 + rh * kD + x;
+                pl = a.l1 + rh;
+            }
+        };
+        for (int c = 0; c < n_parts; c += 2) {
+            const float *po0, *pl0, *po1, *pl1;
+            part(c, po0, pl0);
+            part(min(c + 1, n_parts - 1), po1, pl1);
+            const float la = load_coherent1(pl0);
+            const float lb = load_coherent1(pl1);
+            float4 xa, xb;
+            load_coherent_pair(po0, po1, xa, xb);
+            fold_add(f, la, xa);
+            if (c + 1 < n_parts) fold_add(f, lb, xb);
+        }
+        float4 r;
+        const float lse = fold_result(f, r);
+        store_out4<true>(a.o_out, rh * kD + x, r.x, r.y, r.z, r.w);
+        if (x == 0 && a.lse_out != nullptr) a.lse_out[rh] = lse;
+    }
+}
+
+template <int RHO>
+hipError_t launch_for_rho(const HFusedArgs& a, int wpi, hipStream_t stream) {
+    const int tiles = a.n_prefix_tiles + a.n_suffix_tiles;
+#define BLLM_LAUNCH_HFUSED(W)                                                                                   \
+    hipLaunchKernelGGL((hfused_attention_kernel<RHO, W>), dim3(tiles + (a.n_suffix_rows * W + 3) / 4), dim3(kThreads), \
+                       0, stream, a)
+    switch (wpi) {
+        case 1: BLLM_LAUNCH_HFUSED(1); break;
+        case 2: BLLM_LAUNCH_HFUSED(2); break;
+        default: BLLM_LAUNCH_HFUSED(4); break;
+    }
+#undef BLLM_LAUNCH_HFUSED
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_hfused_attention(const LaunchCtx& c, const HFusedLists& lists, int suffix_wpi, const void* q,
+                                   const void* k_prefix, const void* v_prefix, const void* k_suffix, const void* v_suffix,
+                                   float* o1, float* l1, float* o2, float* l2, void* o_out, float* lse_out) {
+    if (c.n_rows == 0) return hipSuccess;
+    if (c.desc->dtype != BLLM_BF16 || c.desc->head_dim != 128) return hipErrorInvalidValue;
+    const int rho = c.desc->n_q_heads / c.desc->n_kv_heads;
+    HFusedArgs a;
+    a.prefix_tiles = lists.prefix_tiles;
+    a.suffix_tiles = lists.suffix_tiles;
+    a.suffix_rows = lists.suffix_rows;
+    a.n_prefix_tiles = lists.n_prefix_tiles;
+    a.n_suffix_tiles = lists.n_suffix_tiles;
+    a.n_suffix_rows = lists.n_suffix_rows;
+    a.q = static_cast<const uint16_t*>(q);
+    a.k_prefix = static_cast<const uint16_t*>(k_prefix);
+    a.v_prefix = static_cast<const uint16_t*>(v_prefix);
+    a.k_suffix = static_cast<const uint16_t*>(k_suffix);
+    a.v_suffix = static_cast<const uint16_t*>(v_suffix);
+    a.o1 = o1;
+    a.l1 = l1;
+    a.o2 = o2;
+    a.l2 = l2;
+    a.ws_o = lists.ws_o;
+    a.ws_lse = lists.ws_lse;
+    a.prefix_row_split = lists.prefix_row_split;
+    a.arrivals = lists.arrivals;
+    a.o_out = o_out;
+    a.lse_out = lse_out;
+    a.n_q_heads = c.desc->n_q_heads;
+    a.n_kv_heads = c.desc->n_kv_heads;
+    a.log2_rho = rho == 1 ? 0 : rho == 2 ? 1 : rho == 4 ? 2 : 3;
+    a.n_request_rows = lists.n_request_rows;
+    a.scale = c.scale;
+    switch (rho) {
+        case 1: return launch_for_rho<1>(a, suffix_wpi, c.stream);
+        case 2: return launch_for_rho<2>(a, suffix_wpi, c.stream);
+        case 4: return launch_for_rho<4>(a, suffix_wpi, c.stream);
+        case 8: return launch_for_rho<8>(a, suffix_wpi, c.stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace bllm

@@ -1,444 +1,20 @@
-// Matrix-core partial attention for bf16, head_dim 128: a block of query rows
-// (all rows of a prefix-sharing group x the query heads that share one KV head,
-// or the rows of one prefill chunk) against a range of KV rows.
-//
-// This is the shared-prefix part of prefix-shared attention (BatchLLM
-// Sec. 4.3.3, Sec. 5): because every query of the group sees the same keys, the
-// per-request matrix-vector products become one matrix-matrix product and each
-// KV tile is fetched once per workgroup for all its stacked query rows.  The
-// same kernel, with the causal bound of a prefill chunk, serves the chunk rows
-// of the distinct part.
-//
-// Layout of the computation (per wavefront: 32 stacked query rows, 64 KV rows a step):
-//   S^T = K Q^T      A operand = K rows from LDS, B operand = Q held in registers
-//   O^T += V^T P^T   A operand = V^T from LDS, B operand = P straight from the
-//                    S^T accumulators
-// Working on the transposes puts one query per lane column, so the running
-// maximum, the running sum and the rescale factor are per-lane scalars.  The
-// reference maximum is raised lazily (only when a tile exceeds it by 2^8), so
-// the common step needs no cross-lane exchange and no rescale of O.
-//
-// Data movement: K and V tiles go from HBM straight into LDS (16-byte
-// direct-to-LDS loads, no register staging), row-major with the 16-byte units
-// of each row XOR-swizzled against bank conflicts; the swizzle is applied on
-// the global side, by choosing which unit a lane fetches.  V is transposed on
-// its way out of LDS by the transposing 64-bit read, which also lets the lanes
-// pick the KV rows in the order the S^T accumulators hold them
-// (kv = 8i + 4h + j).  Tiles are double-buffered; one barrier per step.
-#include "bllm_device.h"
-#include "bllm_internal.h"
+// Kernel and launcher of the matrix-core partial attention; the device code is in
+// tile_attention_body.h.
+#include "tile_attention_body.h"
 
 namespace bllm {
 namespace {
 
-typedef __attribute__((address_space(3))) void* lds_void_ptr;
-typedef short short4v __attribute__((ext_vector_type(4)));
-typedef short short8v __attribute__((ext_vector_type(8)));
-typedef __attribute__((address_space(3))) short4v* lds_short4_ptr;
+using namespace tile_detail;
 
-constexpr int kD = 128;
-constexpr int kRowBytes = kD * 2;             // one K or V row of one head in LDS
-
-// physical 16-byte unit of logical unit u in LDS row r
-__device__ __forceinline__ int k_unit(int u, int r) { return u ^ (r & 15); }
-__device__ __forceinline__ int v_unit(int u, int r) { return u ^ ((r & 3) << 2); }
-
-// The running maximum is only raised when a tile exceeds it by more than this many powers of
-// two; below that the stale maximum is exact arithmetic anyway (weights up to 2^8, fp32 sums).
-constexpr float kMaxSlack = 8.f;
-
-// gfx950-only instructions live in small device functions whose bodies exist in the device
-// pass only: the host pass cannot type-check these builtins, and a kernel template whose body
-// fails there silently loses its launch stub.
-__device__ __forceinline__ void dma16_to_lds(const unsigned char* gptr, unsigned char* lds_wave_base) {
-#if defined(__HIP_DEVICE_COMPILE__)
-    // every lane moves 16 bytes from its own global address to lds_wave_base + 16 * lane
-    __builtin_amdgcn_global_load_lds(gptr, (lds_void_ptr)lds_wave_base, 16, 0, 0);
-#endif
-}
-
-// s_waitcnt vmcnt(kN) only: wait until at most kN of this wavefront's vector-memory operations
-// (here: direct-to-LDS loads, which complete in order) are still in flight
-template <int kN>
-__device__ __forceinline__ void wait_vector_memory() {
-    static_assert(kN >= 0 && kN < 64, "vmcnt is a 6-bit field");
-#if defined(__HIP_DEVICE_COMPILE__)
-    __builtin_amdgcn_s_waitcnt(0x0F70 | (kN & 15) | ((kN >> 4) << 14));
-#endif
-}
-
-// Transposing 64-bit LDS read of 16-bit elements: inside each group of 16 lanes, lane i receives
-// element i % 4 of the four 8-byte chunks addressed by lanes i / 4, 4 + i / 4, 8 + i / 4, 12 + i / 4.
-__device__ __forceinline__ short4v lds_read_tr16(const unsigned char* lds_addr) {
-#if defined(__HIP_DEVICE_COMPILE__)
-    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)lds_addr);
-#else
-    return short4v{0, 0, 0, 0};
-#endif
-}
-
-// NW wavefronts per workgroup, 32 stacked query rows each.  With about 200 registers a
-// wavefront, two wavefronts share a SIMD, so one runs its exp / convert work on the vector
-// ALUs while the other keeps the matrix cores busy.  BN KV rows per step.
 template <int NW, int BN>
 __global__ __launch_bounds__(64 * NW, 2) void tile_attention_kernel(
     const Item* __restrict__ items, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const uint16_t* __restrict__ v, float* __restrict__ o_part, float* __restrict__ lse_part, float* __restrict__ ws_o,
     float* __restrict__ ws_lse, int n_q_heads, int n_kv_heads, int log2_rho, float scale, MergeTarget mt) {
-    constexpr int kBN = BN;
-    constexpr int kKvb = BN / 32;                    // 32-row blocks of S^T per step
-    constexpr int kTileBytes = kBN * kRowBytes;
-    constexpr int kBufBytes = 2 * kTileBytes;        // K tile + V tile
-    // Two tile buffers, each [K tile | V tile].  They are separate objects on purpose: the
-    // compiler then knows that reading one cannot touch the other, and does not make the reads
-    // of the current tile wait for the direct-to-LDS loads of the next one.
-    __shared__ __attribute__((aligned(1024))) unsigned char smem_even[kBufBytes];
-    __shared__ __attribute__((aligned(1024))) unsigned char smem_odd[kBufBytes];
-
-    const Item it = items[blockIdx.x];
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wavefront-uniform, kept in a scalar register
-    const int col = lane & 31;       // query column of this lane; also the A-operand row
-    const int h = lane >> 5;         // lane half
-    const int rho = 1 << log2_rho;
-    const int head0 = it.kv_head << log2_rho;
-    const int kv_len = it.kv_len;
-    const float c2 = scale * kLog2e;
-
-    float* dst_o;
-    float* dst_l;
-    if (it.dst_row >= 0) {
-        dst_o = ws_o + (static_cast<size_t>(it.dst_row) * n_q_heads + head0) * kD;
-        dst_l = ws_lse + static_cast<size_t>(it.dst_row) * n_q_heads + head0;
-    } else {
-        dst_o = o_part + (static_cast<size_t>(it.q_row0) * n_q_heads + head0) * kD;
-        dst_l = lse_part + static_cast<size_t>(it.q_row0) * n_q_heads + head0;
-    }
-
-    // stacked row m = 32*wave + col  ->  token row m >> log2_rho, head m & (rho-1)
-    const int m_row = 32 * wave + col;
-    const int tok = m_row >> log2_rho;
-    const int hd = m_row & (rho - 1);
-    const bool row_ok = tok < it.n_rows;
-    const int vis = (row_ok && it.vis0 + tok < kv_len) ? it.vis0 + tok : kv_len;   // padding rows see everything
-
-    // (row, head) index of this lane's query in the [n_rows, Hq] arrays of a fused merge
-    const size_t rh = static_cast<size_t>(it.q_row0 + tok) * n_q_heads + head0 + hd;
-    // Fused merge: the other part of this lane's row is one partial result (row of mt.o_a / mt.lse_a)
-    // or, for a row with split KV ranges, n_other partial results in the split workspace.
-    RowSplit sp{0, 0, 0};
-    if (mt.o_a != nullptr && mt.row_split != nullptr && row_ok) sp = mt.row_split[it.q_row0 + tok];
-    const int n_other = sp.n_splits > 0 ? sp.n_splits : 1;
-    auto other_o = [&](int c) -> const float* {
-        return sp.n_splits > 0 ? mt.ws_o + (static_cast<size_t>(sp.ws_row0 + c * sp.stride) * n_q_heads + head0 + hd) * kD
-                               : mt.o_a + rh * kD;
-    };
-    auto other_l = [&](int c) -> float {
-        return sp.n_splits > 0 ? mt.ws_lse[static_cast<size_t>(sp.ws_row0 + c * sp.stride) * n_q_heads + head0 + hd]
-                               : mt.lse_a[rh];
-    };
-    // folds the other part's partials at element x, then this part's (lb, o2); stores 4 elements
-    auto fold_and_store = [&](int x, float lb, const float4& o2) -> float {
-        PartialFold f;
-        for (int c = 0; c < n_other; ++c) fold_add(f, other_l(c), *reinterpret_cast<const float4*>(other_o(c) + x));
-        fold_add(f, lb, o2);
-        float4 r;
-        const float lse = fold_result(f, r);
-        store_out4<true>(mt.o_out, rh * kD + x, r.x, r.y, r.z, r.w);
-        return lse;
-    };
-    if (kv_len <= 0 && mt.o_a != nullptr) {      // empty part, fused merge: the other part passes through
-        if (row_ok) {
-            float lse = -INFINITY;
-            for (int x = h * 64; x < h * 64 + 64; x += 4) lse = fold_and_store(x, -INFINITY, make_float4(0.f, 0.f, 0.f, 0.f));
-            if (h == 0 && mt.lse_out != nullptr) mt.lse_out[rh] = lse;
-        }
-        return;
-    }
-    if (kv_len <= 0) {               // empty part: output 0, log-sum-exp -inf
-        if (row_ok) {
-            float* orow = dst_o + (static_cast<size_t>(tok) * n_q_heads + hd) * kD;
-            for (int x = h * 64; x < h * 64 + 64; x += 4) *reinterpret_cast<float4*>(orow + x) = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (h == 0) dst_l[static_cast<size_t>(tok) * n_q_heads + hd] = -INFINITY;
-        }
-        return;
-    }
-
-    // smallest visible count among this wavefront's rows: tiles that end below it need no mask
-    const int wave_tok_lo = (32 * wave) >> log2_rho;
-    const int wave_min_vis = wave_tok_lo < it.n_rows ? min(kv_len, it.vis0 + wave_tok_lo) : kv_len;
-
-    // ---- Q fragments (B operand of S^T = K Q^T): Q[query = col][d = 16 t + 8 h + 0..7] -------
-    bf16x8 qreg[8];
-    {
-        const uint16_t* qrow = q + (static_cast<size_t>(it.q_row0 + tok) * n_q_heads + head0 + hd) * kD + 8 * h;
-#pragma unroll
-        for (int t = 0; t < 8; ++t) {
-            const uint4 raw = row_ok ? *reinterpret_cast<const uint4*>(qrow + 16 * t) : make_uint4(0, 0, 0, 0);
-            qreg[t] = __builtin_bit_cast(bf16x8, raw);
-        }
-    }
-
-    floatx16 oacc[4];
-#pragma unroll
-    for (int db = 0; db < 4; ++db)
-#pragma unroll
-        for (int x = 0; x < 16; ++x) oacc[db][x] = 0.f;
-    float m_run = -INFINITY;         // reference maximum, in log2 units (score * c2)
-    float l_run = 0.f;               // this lane's share of the running sum
-
-    // ---- HBM -> LDS: a wavefront instruction moves 4 rows (1 KB); a K or V tile is 16 of them.
-    // Instruction j of a tile fills LDS rows 4j .. 4j+3; lane l fills row 4j + l/16, physical
-    // unit l%16, i.e. it fetches the logical unit that the swizzle maps there.
-    constexpr int kInstrPerWave = kBN / 4 / NW;     // per matrix per tile
-    static_assert(kInstrPerWave >= 1, "tile too small for this many wavefronts");
-    const uint32_t row_bytes = static_cast<uint32_t>(n_kv_heads) * kRowBytes;
-    const size_t tile_stride = static_cast<size_t>(row_bytes) * kBN;
-    const unsigned char* kg = reinterpret_cast<const unsigned char*>(k) +
-                              (static_cast<size_t>(it.kv_row0) * n_kv_heads + it.kv_head) * kRowBytes;
-    const unsigned char* vg = reinterpret_cast<const unsigned char*>(v) +
-                              (static_cast<size_t>(it.kv_row0) * n_kv_heads + it.kv_head) * kRowBytes;
-    const int n_tiles = (kv_len + kBN - 1) / kBN;
-    uint32_t goff_k[kInstrPerWave], goff_v[kInstrPerWave];
-#pragma unroll
-    for (int jj = 0; jj < kInstrPerWave; ++jj) {
-        const int r = 4 * (wave * kInstrPerWave + jj) + (lane >> 4);
-        goff_k[jj] = r * row_bytes + (k_unit(lane & 15, r) << 4);
-        goff_v[jj] = r * row_bytes + (v_unit(lane & 15, r) << 4);
-    }
-    // One K and one V instruction (index jj) of a tile; `full` tiles use the precomputed offsets.
-    auto dma_part = [&](int tile, unsigned char* dst_buf, int jj, bool full) {
-        // tile base pointers stay in scalar registers (the empty asm keeps the loop optimiser from
-        // turning base + lane offset into one running 64-bit vector pointer per instruction)
-        uint64_t kt_bits = reinterpret_cast<uint64_t>(kg + tile * tile_stride);
-        uint64_t vt_bits = reinterpret_cast<uint64_t>(vg + tile * tile_stride);
-        asm volatile("" : "+s"(kt_bits), "+s"(vt_bits));
-        const unsigned char* kt = reinterpret_cast<const unsigned char*>(kt_bits);
-        const unsigned char* vt = reinterpret_cast<const unsigned char*>(vt_bits);
-        unsigned char* lds_k = dst_buf + (wave * kInstrPerWave + jj) * 1024;
-        unsigned char* lds_v = lds_k + kTileBytes;
-        if (full) {
-            // keep the lane offsets 32-bit up to the instruction (scalar base + 32-bit offset form)
-            uint32_t ok = goff_k[jj], ov = goff_v[jj];
-            asm volatile("" : "+v"(ok), "+v"(ov));
-            dma16_to_lds(kt + ok, lds_k);
-            dma16_to_lds(vt + ov, lds_v);
-        } else {
-            // last tile of the range: rows past the end re-read the last row (their scores are masked)
-            const int rows_left = kv_len - tile * kBN;
-            const int r = 4 * (wave * kInstrPerWave + jj) + (lane >> 4);
-            const int rc = min(r, rows_left - 1);
-            dma16_to_lds(kt + (rc * row_bytes + (k_unit(lane & 15, r) << 4)), lds_k);
-            dma16_to_lds(vt + (rc * row_bytes + (v_unit(lane & 15, r) << 4)), lds_v);
-        }
-    };
-    auto dma_tile = [&](int tile, unsigned char* dst_buf) {
-        const bool full = kv_len - tile * kBN >= kBN;
-#pragma unroll
-        for (int jj = 0; jj < kInstrPerWave; ++jj) dma_part(tile, dst_buf, jj, full);
-    };
-
-    // ---- LDS read addresses ---------------------------------------------------------------------
-    // K (A operand of S^T): lane (row = col, half h) reads unit 2t + h of row 32 kvb + col.
-    uint32_t ka[8];
-#pragma unroll
-    for (int t = 0; t < 8; ++t) ka[t] = col * kRowBytes + (k_unit(2 * t + h, col) << 4);
-    // V (A operand of O^T) through the transposing read: inside a group of 16 lanes, lane i = 4e + c
-    // addresses the 8 bytes V[row(e)][32 db + 16 g1 + 4c ..+3] and receives V[row(0..3)][32 db + col];
-    // row(e) = 32 kvb + 16 u + 8 a + 4 h + e are the KV rows of accumulator registers 8u + 4a + e.
-    uint32_t va[4];
-    {
-        const int e = (lane >> 2) & 3;
-        const int c = lane & 3;
-        const int g1 = (lane >> 4) & 1;
-#pragma unroll
-        for (int db = 0; db < 4; ++db)
-            va[db] = kTileBytes + (4 * h + e) * kRowBytes + (v_unit(4 * db + 2 * g1 + (c >> 1), e) << 4) + (c & 1) * 8;
-    }
-
-    dma_tile(0, smem_even);
-    wait_vector_memory<0>();
-    __syncthreads();
-
-    // One step on the tile in `sb`, while the next tile streams into `sb_next`.
-    auto step = [&](int tile, const unsigned char* sb, unsigned char* sb_next) {
-        const int tile_base = tile * kBN;
-        // the other buffer is free: its last readers ran before the previous barrier
-        // The loads of the next tile are issued a few at a time between the groups of matrix
-        // products below, so the wavefront never sits on a full memory queue with nothing else
-        // to issue; a ragged last tile (rare) is issued up front.
-        const bool dma_next = tile + 1 < n_tiles;
-        const bool dma_spread = dma_next && kv_len - (tile + 1) * kBN >= kBN;
-        if (dma_next && !dma_spread) dma_tile(tile + 1, sb_next);
-
-        // ---- S^T = K Q^T (64 kv x 32 queries) ---------------------------------------------------
-        floatx16 sacc[kKvb];
-        {
-            // K fragments are requested one group (two k-steps) ahead of the products that use
-            // them, so their LDS latency hides behind the previous group's products
-            constexpr int kGroups = 4;                 // groups of 2 k-steps
-            uint4 kf[2][2][kKvb];                      // [parity][k-step in group][kvb]
-            auto request = [&](int g, uint4 (&dst)[2][kKvb]) {
-#pragma unroll
-                for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-                    for (int kvb = 0; kvb < kKvb; ++kvb)
-                        dst[tt][kvb] = *reinterpret_cast<const uint4*>(sb + ka[2 * g + tt] + kvb * 32 * kRowBytes);
-            };
-            const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-            request(0, kf[0]);
-#pragma unroll
-            for (int g = 0; g < kGroups; ++g) {
-                if (g + 1 < kGroups) request(g + 1, kf[(g + 1) & 1]);
-                if (dma_spread) {
-#pragma unroll
-                    for (int jj = g * kInstrPerWave / kGroups; jj < (g + 1) * kInstrPerWave / kGroups; ++jj)
-                        dma_part(tile + 1, sb_next, jj, true);
-                }
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-                    for (int kvb = 0; kvb < kKvb; ++kvb)
-                        sacc[kvb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            __builtin_bit_cast(bf16x8, kf[g & 1][tt][kvb]), qreg[2 * g + tt],
-                            (g == 0 && tt == 0) ? zero : sacc[kvb], 0, 0, 0);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        }
-        if (tile_base + kBN > wave_min_vis) {       // last tile(s) of an item: mask what a row cannot see
-#pragma unroll
-            for (int kvb = 0; kvb < kKvb; ++kvb)
-#pragma unroll
-                for (int x = 0; x < 16; ++x) {
-                    const int kvi = tile_base + 32 * kvb + 8 * (x >> 2) + 4 * h + (x & 3);
-                    sacc[kvb][x] = kvi >= vis ? -INFINITY : sacc[kvb][x];
-                }
-            asm volatile("" ::: "memory");           // keep it a branch
-        }
-        // ---- reference maximum: raised (and O, l rescaled) only when exceeded by kMaxSlack ------
-        float mx = -INFINITY;
-#pragma unroll
-        for (int kvb = 0; kvb < kKvb; ++kvb)
-#pragma unroll
-            for (int x = 0; x < 16; ++x) mx = fmaxf(mx, sacc[kvb][x]);
-        const float zloc = mx * c2;
-        if (__any(zloc > m_run + kMaxSlack)) {
-            const float z = fmaxf(zloc, __shfl_xor(zloc, 32));
-            const float m_new = fmaxf(m_run, z);
-            // first tile: m_run = -inf and m_new is finite (KV row 0 is visible to every row)
-            float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-            asm volatile("" : "+v"(alpha));          // rare path: must stay behind its branch
-            l_run *= alpha;
-            m_run = m_new;
-#pragma unroll
-            for (int db = 0; db < 4; ++db)
-#pragma unroll
-                for (int x = 0; x < 16; ++x) oacc[db][x] *= alpha;
-        }
-        // ---- P = exp2(S c2 - m) in bf16, running sum -------------------------------------------
-        bf16x8 pb[kKvb][2];          // [kvb][u]
-        float lsum = 0.f;
-#pragma unroll
-        for (int kvb = 0; kvb < kKvb; ++kvb)
-#pragma unroll
-            for (int u = 0; u < 2; ++u)
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const float p = __builtin_amdgcn_exp2f(fmaf(sacc[kvb][8 * u + e], c2, -m_run));
-                    lsum += p;
-                    pb[kvb][u][e] = static_cast<__bf16>(p);
-                }
-        l_run += lsum;
-        // ---- O^T += V^T P^T ---------------------------------------------------------------------
-#pragma unroll
-        for (int kvb = 0; kvb < kKvb; ++kvb) {
-#pragma unroll
-            for (int u = 0; u < 2; ++u) {
-#pragma unroll
-                for (int db = 0; db < 4; ++db) {
-                    const unsigned char* base = sb + va[db] + (32 * kvb + 16 * u) * kRowBytes;
-                    const short4v lo = lds_read_tr16(base);
-                    const short4v hi = lds_read_tr16(base + 8 * kRowBytes);
-                    const short8v a = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                    oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), pb[kvb][u], oacc[db], 0, 0, 0);
-                }
-            }
-        }
-        // Own loads of the next tile have landed; after the barrier everybody's have, and
-        // everybody is done reading this tile.
-        wait_vector_memory<0>();
-        __syncthreads();
-    };
-    for (int tile = 0; tile < n_tiles; tile += 2) {
-        step(tile, smem_even, smem_odd);
-        if (tile + 1 < n_tiles) step(tile + 1, smem_odd, smem_even);
-    }
-
-    // ---- epilogue: normalise and store O (transposed back), log-sum-exp --------------------------
-    const float ltot = l_run + __shfl_xor(l_run, 32);
-    if (row_ok && mt.o_a != nullptr) {
-        // Fused merge: this part is (O / l, log-sum-exp lb), the other part comes from memory.  The
-        // weights of all parts (relative to their common maximum) come first, then every partial
-        // is added with its 16 row pieces fetched at once.
-        const float lb = (m_run + log2f(ltot)) * kLn2;          // finite: at least one key is visible
-        float top = lb;
-        for (int c = 0; c < n_other; ++c) top = fmaxf(top, other_l(c));
-        const float w_own = expf(lb - top);
-        float den = w_own;
-        for (int c = 0; c < n_other; ++c) {
-            const float lc = other_l(c);
-            if (lc != -INFINITY) den += expf(lc - top);
-        }
-        const float inv_den = 1.f / den;
-        const float s_own = w_own * inv_den / ltot;
-#pragma unroll
-        for (int db = 0; db < 4; ++db)
-#pragma unroll
-            for (int x = 0; x < 16; ++x) oacc[db][x] *= s_own;
-        for (int c = 0; c < n_other; ++c) {
-            const float lc = other_l(c);
-            if (lc == -INFINITY) continue;                       // an empty partial's rows are never touched
-            const float wc = expf(lc - top) * inv_den;
-            const float* src = other_o(c);
-            float4 xs[16];
-#pragma unroll
-            for (int db = 0; db < 4; ++db)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) xs[4 * db + i] = *reinterpret_cast<const float4*>(src + 32 * db + 8 * i + 4 * h);
-#pragma unroll
-            for (int db = 0; db < 4; ++db)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    oacc[db][4 * i] = fmaf(wc, xs[4 * db + i].x, oacc[db][4 * i]);
-                    oacc[db][4 * i + 1] = fmaf(wc, xs[4 * db + i].y, oacc[db][4 * i + 1]);
-                    oacc[db][4 * i + 2] = fmaf(wc, xs[4 * db + i].z, oacc[db][4 * i + 2]);
-                    oacc[db][4 * i + 3] = fmaf(wc, xs[4 * db + i].w, oacc[db][4 * i + 3]);
-                }
-        }
-#pragma unroll
-        for (int db = 0; db < 4; ++db)
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                store_out4<true>(mt.o_out, rh * kD + 32 * db + 8 * i + 4 * h, oacc[db][4 * i], oacc[db][4 * i + 1],
-                                 oacc[db][4 * i + 2], oacc[db][4 * i + 3]);
-        if (h == 0 && mt.lse_out != nullptr) mt.lse_out[rh] = top + logf(den);
-    } else if (row_ok) {
-        const float inv = 1.f / ltot;
-        float* orow = dst_o + (static_cast<size_t>(tok) * n_q_heads + hd) * kD;
-#pragma unroll
-        for (int db = 0; db < 4; ++db)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const float4 o4 = make_float4(oacc[db][4 * i] * inv, oacc[db][4 * i + 1] * inv, oacc[db][4 * i + 2] * inv,
-                                              oacc[db][4 * i + 3] * inv);
-                *reinterpret_cast<float4*>(orow + 32 * db + 8 * i + 4 * h) = o4;
-            }
-        if (h == 0) dst_l[static_cast<size_t>(tok) * n_q_heads + hd] = (m_run + log2f(ltot)) * kLn2;
-    }
+    tile_attention_body<NW, BN>(items[blockIdx.x], q, k, v, o_part, lse_part, ws_o, ws_lse, n_q_heads, n_kv_heads, log2_rho,
+                                scale, mt);
 }
-
 
 }  // namespace
 

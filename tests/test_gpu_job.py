@@ -52,9 +52,9 @@ def test_job_end_to_end(dtype, hq, hkv, d, s_chunk, m):
             assert np.array_equal(got["kv"][name], vals[name]), (n_it, name)
         ref = run_oracle(batch, vals)
         tol = TOL[dtype]
-        for k in ("o", "o_fused", "o_one_call"):
+        for k in ("o", "o_fused", "o_one_call") + (("o_single", "o_single_again") if "o_single" in got else ()):
             assert max_abs_err(got[k], ref["o"]) <= tol, (n_it, k)
-        for k in ("lse", "lse_fused", "lse_one_call"):
+        for k in ("lse", "lse_fused", "lse_one_call") + (("lse_single", "lse_single_again") if "o_single" in got else ()):
             assert max_abs_err(got[k], ref["lse"]) <= (1e-4 if dtype == workload.BF16 else tol), (n_it, k)
         tokens += batch.n_rows
         n_it += 1

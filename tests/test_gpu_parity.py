@@ -25,6 +25,12 @@ def check_all(batch, vals, scale=0.0, rows=None, requests=None, prefix_groups=No
     # the one-call entry point (split prefixes folded piece by piece in the suffix kernels)
     errs["o_one_call"] = max_abs_err(got["o_one_call"], ref["o"], rows)
     errs["lse_one_call"] = max_abs_err(got["lse_one_call"], ref["lse"], rows)
+    # the single-launch form (last arrival reduces), first and second call
+    if "o_single" in got:
+        for k in ("o_single", "o_single_again"):
+            errs[k] = max_abs_err(got[k], ref["o"], rows)
+        for k in ("lse_single", "lse_single_again"):
+            errs[k] = max_abs_err(got[k], ref["lse"], rows)
     print(batch.name, "T=%d" % batch.n_rows, {k: "%.2e" % v for k, v in errs.items()}, flush=True)
     # fp32 path: everything within 1e-5.  bf16 path: the merged output (rounded to bf16)
     # within 2e-2; the fp32 partial outputs within 1e-2 (the matrix-core P.V product rounds the
@@ -32,7 +38,7 @@ def check_all(batch, vals, scale=0.0, rows=None, requests=None, prefix_groups=No
     # log-sum-exp comes from fp32 scores of exact bf16 products and stays within 1e-4.
     bf16 = batch.layer.dtype == workload.BF16
     for k, v in errs.items():
-        bound = tol if k in ("o", "o_fused", "o_one_call") else (1e-4 if k.startswith("lse") else 1e-2) if bf16 else tol
+        bound = tol if k in ("o", "o_fused", "o_one_call", "o_single", "o_single_again") else (1e-4 if k.startswith("lse") else 1e-2) if bf16 else tol
         assert v <= bound, (k, v, bound)
     return got, ref
 
@@ -354,9 +360,9 @@ def test_decode_batch_with_a_prefix_chunk_sampled():
     row0 = np.concatenate([[0], np.cumsum(b.req_q_len)])
     rows = np.concatenate([np.arange(row0[r], row0[r + 1]) for r in reqs])
     tol = TOL[workload.BF16]
-    for k in ("o", "o_fused", "o_one_call"):
+    for k in ("o", "o_fused", "o_one_call", "o_single", "o_single_again"):
         assert max_abs_err(got[k], ref["o"], rows) <= tol, k
-    for k in ("lse", "lse_fused", "lse_one_call"):
+    for k in ("lse", "lse_fused", "lse_one_call", "lse_single", "lse_single_again"):
         assert max_abs_err(got[k], ref["lse"], rows) <= 1e-4, k
     # sampled prefix rows: position p of the new group is the only query row of a one-group batch
     # whose prefix ends at p
@@ -369,9 +375,9 @@ def test_decode_batch_with_a_prefix_chunk_sampled():
         r1 = run_oracle(one, dict(q=v["q"][t:t + 1], k_prefix=v["k_prefix"][k0:k0 + pos + 1],
                                   v_prefix=v["v_prefix"][k0:k0 + pos + 1], k_suffix=v["k_suffix"][:0],
                                   v_suffix=v["v_suffix"][:0]))
-        for k in ("o", "o_fused", "o_one_call"):
+        for k in ("o", "o_fused", "o_one_call", "o_single", "o_single_again"):
             assert max_abs_err(got[k][t:t + 1], r1["o"]) <= tol, (k, pos)
-        for k in ("lse", "lse_fused", "lse_one_call", "lse_prefix"):
+        for k in ("lse", "lse_fused", "lse_one_call", "lse_prefix", "lse_single", "lse_single_again"):
             assert max_abs_err(got[k][t:t + 1], r1["lse"]) <= 1e-4, (k, pos)
         assert max_abs_err(got["o_prefix"][t:t + 1], r1["o"]) <= 1e-2
     pre = np.arange(b.n_request_rows, b.n_rows)
