@@ -115,16 +115,28 @@ __device__ __forceinline__ void coherent_stores_done() {
 __device__ __forceinline__ float load_coherent1(const float* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-// two coherent 16-byte loads in flight together, then the wait; the results are tied to the wait
-__device__ __forceinline__ void load_coherent_pair(const float* pa, const float* pb, float4& a, float4& b) {
+// a 16-byte coherent load the compiler keeps track of (four single-word ones): for loads that stay in
+// flight behind other work
+__device__ __forceinline__ float4 load_coherent4_tracked(const float* p) {
+    return make_float4(load_coherent1(p), load_coherent1(p + 1), load_coherent1(p + 2), load_coherent1(p + 3));
+}
+// six coherent 16-byte loads in flight together, then the wait; the results are tied to the wait
+__device__ __forceinline__ void load_coherent_six(const float* const (&p)[6], float4 (&x)[6]) {
 #if defined(__HIP_DEVICE_COMPILE__)
-    float4r va, vb;
-    asm volatile("global_load_dwordx4 %0, %2, off sc1\n\tglobal_load_dwordx4 %1, %3, off sc1\n\ts_waitcnt vmcnt(0)"
-                 : "=&v"(va), "=&v"(vb)
-                 : "v"(pa), "v"(pb)
-                 : "memory");
-    a = make_float4(va[0], va[1], va[2], va[3]);
-    b = make_float4(vb[0], vb[1], vb[2], vb[3]);
+    float4r v0, v1, v2, v3, v4, v5;
+    asm volatile(
+        "global_load_dwordx4 %0, %6, off sc1\n\tglobal_load_dwordx4 %1, %7, off sc1\n\t"
+        "global_load_dwordx4 %2, %8, off sc1\n\tglobal_load_dwordx4 %3, %9, off sc1\n\t"
+        "global_load_dwordx4 %4, %10, off sc1\n\tglobal_load_dwordx4 %5, %11, off sc1\n\ts_waitcnt vmcnt(0)"
+        : "=&v"(v0), "=&v"(v1), "=&v"(v2), "=&v"(v3), "=&v"(v4), "=&v"(v5)
+        : "v"(p[0]), "v"(p[1]), "v"(p[2]), "v"(p[3]), "v"(p[4]), "v"(p[5])
+        : "memory");
+    x[0] = make_float4(v0[0], v0[1], v0[2], v0[3]);
+    x[1] = make_float4(v1[0], v1[1], v1[2], v1[3]);
+    x[2] = make_float4(v2[0], v2[1], v2[2], v2[3]);
+    x[3] = make_float4(v3[0], v3[1], v3[2], v3[3]);
+    x[4] = make_float4(v4[0], v4[1], v4[2], v4[3]);
+    x[5] = make_float4(v5[0], v5[1], v5[2], v5[3]);
 #endif
 }
 

@@ -8,7 +8,10 @@
 // passes do; then it ARRIVES at the counter of each (token row, KV head) it covered.  The part
 // that arrives last at a counter reduces all partials of that row and head through online
 // softmax and writes the final output (Sec. 5).  Nobody waits for anybody: there is no spinning,
-// every workgroup runs to its end whatever the others do.
+// every workgroup runs to its end whatever the others do.  A streaming item that finds, when it
+// starts, that every prefix part of its row has already arrived is certain to be the last: it
+// fetches those partials behind its own KV stream, folds them with its result in registers and
+// writes the final output directly, with no partial of its own.
 //
 // Ordering: the partial results are written with device-scope atomic stores (they go through to
 // the level all compute dies share); the barrier of the workgroup waits until every wavefront's
@@ -77,13 +80,53 @@ __global__ __launch_bounds__(kThreads, RHO == 8 ? 1 : 2) void hfused_attention_k
         unit_head = it.kv_head;
     } else {
         const int sb = b - a.n_prefix_tiles - a.n_suffix_tiles;
-        stream_detail::stream_attention_body<true, kD, RHO, WPI, false, true>(sb, a.suffix_rows, a.n_suffix_rows, a.q, a.k_suffix,
-                                                                        a.v_suffix, a.o2, a.l2, a.ws_o, a.ws_lse, a.n_q_heads,
-                                                                        a.n_kv_heads, a.scale, none);
         const int first = sb * kItemsPerBlock;
-        n_units = min(kItemsPerBlock, a.n_suffix_rows - first);
-        if (tid < n_units) {
-            const Item it = a.suffix_rows[first + tid];
+        // Has every prefix part of the item's row arrived already?  One decision per item, taken by the
+        // first wavefront of the WPI that share it.
+        __shared__ int s_certain[kItemsPerBlock];
+        __shared__ int s_pending[kItemsPerBlock];
+        const int wave = tid >> 6;
+        const int item_in_block = wave / WPI;
+        const int my_item = first + item_in_block;
+        const bool item_ok = my_item < a.n_suffix_rows;
+        int32_t* my_counter = nullptr;
+        if (item_ok) {
+            const Item it = a.suffix_rows[my_item];
+            my_counter = a.arrivals + static_cast<size_t>(it.q_row0) * a.n_kv_heads + it.kv_head;
+            if (tid == item_in_block * WPI * 64) {
+                const RowSplit sp = a.prefix_row_split[it.q_row0];
+                const int arrived = __hip_atomic_load(my_counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                s_certain[item_in_block] = arrived == (sp.n_splits > 0 ? sp.n_splits : 1) ? 1 : 0;
+            }
+        } else if (tid == item_in_block * WPI * 64) {
+            s_certain[item_in_block] = 0;
+        }
+        __syncthreads();
+        const bool certain_last = s_certain[item_in_block] != 0;
+        MergeTarget mt{};
+        if (certain_last) {
+            mt.o_a = a.o1;
+            mt.lse_a = a.l1;
+            mt.o_out = a.o_out;
+            mt.lse_out = a.lse_out;
+            mt.row_split = a.prefix_row_split;
+            mt.ws_o = a.ws_o;
+            mt.ws_lse = a.ws_lse;
+        }
+        stream_detail::stream_attention_body<true, kD, RHO, WPI, true, true>(sb, a.suffix_rows, a.n_suffix_rows, a.q, a.k_suffix,
+                                                                       a.v_suffix, a.o2, a.l2, a.ws_o, a.ws_lse, a.n_q_heads,
+                                                                       a.n_kv_heads, a.scale, mt);
+        if (tid == item_in_block * WPI * 64) {
+            // a certain-last item has written the final output: its counter goes back to zero for the next
+            // call; any other item still has to arrive
+            if (certain_last) atomicExch(my_counter, 0);
+            s_pending[item_in_block] = (item_ok && !certain_last) ? my_item : -1;
+        }
+        __syncthreads();
+        n_units = kItemsPerBlock;                          // slots; empty ones are skipped below
+        unit_row = -1;
+        if (tid < kItemsPerBlock && s_pending[tid] >= 0) {
+            const Item it = a.suffix_rows[s_pending[tid]];
             unit_row = it.q_row0;
             unit_head = it.kv_head;
         }
@@ -92,7 +135,7 @@ __global__ __launch_bounds__(kThreads, RHO == 8 ? 1 : 2) void hfused_attention_k
     // ---- arrive; the last arrival of a (row, KV head) reduces its partials ---------------------
     coherent_stores_done();
     __syncthreads();             // every wavefront's partial stores have completed
-    if (tid < n_units) {
+    if (tid < n_units && unit_row >= 0) {
         const RowSplit sp = a.prefix_row_split[unit_row];
         const int expected = (sp.n_splits > 0 ? sp.n_splits : 1) + (unit_row < a.n_request_rows ? 1 : 0);
         int32_t* counter = a.arrivals + static_cast<size_t>(unit_row) * a.n_kv_heads + unit_head;
@@ -114,7 +157,7 @@ __global__ __launch_bounds__(kThreads, RHO == 8 ? 1 : 2) void hfused_attention_k
         const int head = s_late_head[u] * RHO + p / (kD / 4);
         const int x = 4 * (p % (kD / 4));
         const size_t rh = static_cast<size_t>(row) * a.n_q_heads + head;
-        // the partials of this element, two at a time: prefix pieces (or the one prefix partial), then
+        // the partials of this element, six at a time: prefix pieces (or the one prefix partial), then
         // the suffix partial; an absent one repeats the previous address and is not folded
         PartialFold f;
         const RowSplit sp = a.prefix_row_split[row];
@@ -133,16 +176,20 @@ __global__ __launch_bounds__(kThreads, RHO == 8 ? 1 : 2) void hfused_attention_k
                 pl = a.l1 + rh;
             }
         };
-        for (int c = 0; c < n_parts; c += 2) {
-            const float *po0, *pl0, *po1, *pl1;
-            part(c, po0, pl0);
-            part(min(c + 1, n_parts - 1), po1, pl1);
-            const float la = load_coherent1(pl0);
-            const float lb = load_coherent1(pl1);
-            float4 xa, xb;
-            load_coherent_pair(po0, po1, xa, xb);
-            fold_add(f, la, xa);
-            if (c + 1 < n_parts) fold_add(f, lb, xb);
+        for (int c0 = 0; c0 < n_parts; c0 += 6) {
+            const float* po[6];
+            float l[6];
+            float4 xs[6];
+#pragma unroll
+            for (int i = 0; i < 6; ++i) {
+                const float* pl;
+                part(min(c0 + i, n_parts - 1), po[i], pl);
+                l[i] = load_coherent1(pl);
+            }
+            load_coherent_six(po, xs);
+#pragma unroll
+            for (int i = 0; i < 6; ++i)
+                if (c0 + i < n_parts) fold_add(f, l[i], xs[i]);
         }
         float4 r;
         const float lse = fold_result(f, r);

@@ -190,9 +190,17 @@ __device__ __forceinline__ void stream_attention_body(
                    ? mt.ws_o + (static_cast<size_t>(sp.ws_row0 + c * sp.stride) * n_q_heads + head0 + e) * D
                    : mt.o_a + (rh0 + e) * D;
     };
+    // (kCoherent: the other part was written by workgroups of this same launch)
     auto other_l = [&](int e, int c) -> float {
-        return (kPieces && sp.n_splits > 0) ? mt.ws_lse[static_cast<size_t>(sp.ws_row0 + c * sp.stride) * n_q_heads + head0 + e]
-                               : mt.lse_a[rh0 + e];
+        const float* p = (kPieces && sp.n_splits > 0)
+                             ? mt.ws_lse + static_cast<size_t>(sp.ws_row0 + c * sp.stride) * n_q_heads + head0 + e
+                             : mt.lse_a + rh0 + e;
+        if constexpr (kCoherent) return load_coherent1(p);
+        else return *p;
+    };
+    auto other_x = [&](int e, int c, int d) -> float4 {
+        if constexpr (kCoherent) return load_coherent4_tracked(other_o(e, c) + d);
+        else return *reinterpret_cast<const float4*>(other_o(e, c) + d);
     };
     // the quad with index i of this thread: head e, first element d (false: no such quad)
     auto quad_of = [&](int i, int& e, int& d) -> bool {
@@ -215,7 +223,7 @@ __device__ __forceinline__ void stream_attention_body(
 #pragma unroll
         for (int c = 0; c < kPre; ++c)
             if (c < n_other) fold_add(f, pre_l[i][c], pre_o[i][c]);
-        for (int c = kPre; c < n_other; ++c) fold_add(f, other_l(e, c), *reinterpret_cast<const float4*>(other_o(e, c) + d));
+        for (int c = kPre; c < n_other; ++c) fold_add(f, other_l(e, c), other_x(e, c, d));
         fold_add(f, lb, o2);
         float4 r;
         const float lse = fold_result(f, r);
@@ -397,7 +405,7 @@ __device__ __forceinline__ void stream_attention_body(
 #pragma unroll
                 for (int c = 0; c < kPre; ++c)
                     if (c < n_other) {
-                        pre_o[i][c] = *reinterpret_cast<const float4*>(other_o(e, c) + d);
+                        pre_o[i][c] = other_x(e, c, d);
                         pre_l[i][c] = other_l(e, c);
                     }
             }

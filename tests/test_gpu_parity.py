@@ -232,7 +232,8 @@ def test_one_call_rejects_a_small_or_misaligned_workspace():
 def test_graph_replays_match_eager_launches():
     """The device calls of a step captured in a HIP graph: every replay, with eager work and
     synchronisation in between and with new contents in the same input tensors, gives bit for
-    bit what the eager calls give (both call sequences)."""
+    bit what the eager calls give (every call sequence; the single-launch form, where the timing
+    decides which part reduces a row, to the output's rounding)."""
     import torch
     import paper_2412_03594_amd as bllm
     b = workload.ragged_toy(7, dtype=workload.BF16, n_q_heads=8, n_kv_heads=2, head_dim=128,
@@ -252,8 +253,12 @@ def test_graph_replays_match_eager_launches():
     bufs = {"o1": mk(T, 8, 128), "l1": mk(T, 8), "o2": mk(T, 8, 128), "l2": mk(T, 8),
             "o": mk(T, 8, 128, dt=torch.bfloat16), "lse": mk(T, 8)}
     ws = torch.zeros(bllm.prefix_shared_workspace_bytes(pg) // 4 + 1, device=dev, dtype=torch.float32)
-    for fused in (False, True, "one call"):
-        if fused == "one call":
+    ws2 = torch.zeros(bllm.prefix_shared_single_launch_workspace_bytes(pg) // 4 + 1, device=dev, dtype=torch.float32)
+    for fused in (False, True, "one call", "single launch"):
+        if fused == "single launch":
+            run = lambda: bllm.prefix_shared_attention_single_launch(pg, cur[0], cur[1], cur[2], cur[3], cur[4], ws2,
+                                                                     bufs["o"], bufs["lse"])
+        elif fused == "one call":
             run = lambda: bllm.prefix_shared_attention(pg, cur[0], cur[1], cur[2], cur[3], cur[4], ws, bufs["o"], bufs["lse"])
         else:
             run = lambda: bllm.three_call_attention(pg, cur[0], cur[1], cur[2], cur[3], cur[4], bufs, fused=fused)
@@ -277,7 +282,11 @@ def test_graph_replays_match_eager_launches():
             torch.cuda.synchronize()
             g.replay()
             torch.cuda.synchronize()
-            assert torch.equal(bufs["o"], want_o) and torch.equal(bufs["lse"], want_l), (fused, which)
+            if fused == "single launch":
+                assert (bufs["o"].float() - want_o.float()).abs().max().item() <= 2e-2, which
+                assert (bufs["lse"] - want_l).abs().max().item() <= 1e-5, which
+            else:
+                assert torch.equal(bufs["o"], want_o) and torch.equal(bufs["lse"], want_l), (fused, which)
         del g
     pg.destroy()
 
