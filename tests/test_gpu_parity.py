@@ -164,7 +164,14 @@ def test_empty_batch_is_a_no_op():
     bllm.suffix_attention_merged(pg, None, None, None, None, None, None)
     assert bllm.prefix_shared_workspace_bytes(pg) == 0
     bllm.prefix_shared_attention(pg, None, None, None, None, None, None, None)
+    assert bllm.prefix_shared_single_launch_workspace_bytes(pg) == 0
+    bllm.prefix_shared_attention_single_launch(pg, None, None, None, None, None, torch_empty(), None)
     pg.destroy()
+
+
+def torch_empty():
+    import torch
+    return torch.zeros(0, device="cuda:0", dtype=torch.float32)
 
 
 def test_fused_suffix_pass_drops_rows_of_an_empty_prefix_part():
@@ -225,8 +232,22 @@ def test_one_call_rejects_a_small_or_misaligned_workspace():
     with pytest.raises(bllm.BllmError):
         bllm.prefix_shared_attention(pg, q, kp, kp, ks, ks, big[1:], o)      # 4-byte aligned only
     bllm.prefix_shared_attention(pg, q, kp, kp, ks, ks, big, o)
+    # the single-launch form needs twice that, and covers the matrix-core shapes only
+    assert bllm.prefix_shared_single_launch_workspace_bytes(pg) == 2 * need
+    with pytest.raises(bllm.BllmError) as e:
+        bllm.prefix_shared_attention_single_launch(pg, q, kp, kp, ks, ks, big, o)
+    assert e.value.code == -1
+    big2 = torch.zeros(need // 2 + 8, device=dev, dtype=torch.float32)
+    bllm.prefix_shared_attention_single_launch(pg, q, kp, kp, ks, ks, big2, o)
     torch.cuda.synchronize()
     pg.destroy()
+    pg32 = bllm.prefix_group_create((8, 2, 128, workload.F32, 0.0), [5], [0], [3], [1])
+    f = lambda *shape: torch.zeros(shape, device=dev, dtype=torch.float32)
+    with pytest.raises(bllm.BllmError) as e:
+        bllm.prefix_shared_attention_single_launch(pg32, f(1, 8, 128), f(5, 2, 128), f(5, 2, 128), f(3, 2, 128), f(3, 2, 128),
+                                                   big2, f(1, 8, 128))
+    assert e.value.code == -2
+    pg32.destroy()
 
 
 def test_graph_replays_match_eager_launches():
