@@ -1,6 +1,7 @@
 // C ABI of libbllm: argument validation, handle life cycle, and the sequence of
 // kernel launches behind each call.  See include/bllm.h for the contract.
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 
@@ -274,6 +275,18 @@ static int launch_pass_kernels(const bllm_prefix_groups* pg, bool prefix, const 
     }
     LaunchCtx c = make_ctx(pg, hip_stream);
     hipError_t e;
+    if (!prefix && !tiles.empty() && !rows.empty() && pg->desc.n_q_heads / pg->desc.n_kv_heads <= 4 &&
+        std::getenv("BLLM_TUNE_SUFFIX_SEPARATE") == nullptr) {
+        // prefill chunks and decode rows in one launch: the two kinds of work run beside each other
+        e = launch_suffix_fused(c, pg->d.suffix_tile_items, static_cast<int32_t>(tiles.size()), pg->d.suffix_row_items,
+                                static_cast<int32_t>(rows.size()), p.suffix_stream_wpi, q, k, v, o_part, lse_part,
+                                pg->d.ws_o, pg->d.ws_lse, mt);
+        if (e != hipSuccess) return hip_fail(e, "suffix pass launch");
+        const int32_t row0 = p.group_prefix_row_start[0];
+        e = launch_keyless_rows(c, row0, p.n_rows - row0, o_part, lse_part, mt);
+        if (e != hipSuccess) return hip_fail(e, "keyless rows launch");
+        return BLLM_OK;
+    }
     if (!tiles.empty()) {
         e = launch_tile_attention(c, prefix ? pg->d.prefix_tile_items : pg->d.suffix_tile_items,
                                   static_cast<int32_t>(tiles.size()), p.tile_waves, q, k, v, o_part, lse_part, pg->d.ws_o,

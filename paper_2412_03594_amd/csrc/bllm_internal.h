@@ -111,6 +111,11 @@ hipError_t launch_stream_attention(const LaunchCtx& c, const Item* items, int32_
 hipError_t launch_tile_attention(const LaunchCtx& c, const Item* items, int32_t n_items, int waves, const void* q,
                                  const void* k, const void* v, float* o_part, float* lse_part, float* ws_o,
                                  float* ws_lse, const MergeTarget& mt);
+// Chunk tiles and streaming items of the distinct-suffix pass as workgroups of one launch (bf16, head_dim 128,
+// both lists non-empty).
+hipError_t launch_suffix_fused(const LaunchCtx& c, const Item* tiles, int32_t n_tiles, const Item* rows, int32_t n_rows_items,
+                               int waves_per_item, const void* q, const void* k, const void* v, float* o_part,
+                               float* lse_part, float* ws_o, float* ws_lse, const MergeTarget& mt);
 hipError_t launch_split_combine(const LaunchCtx& c, const RowSplit* row_split, const float* ws_o, const float* ws_lse,
                                 float* o_part, float* lse_part);
 // The whole path as one launch (bf16, head_dim 128 only): prefix tiles, chunk tiles and streaming items as
