@@ -1,0 +1,55 @@
+"""Host-side checks of bench.py's contract that need no GPU: more than one GPU is refused with a
+message, and the algorithmic byte / flop counts agree with a direct count on a small batch."""
+import os
+import subprocess
+import sys
+
+import numpy as np
+
+import workload
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_more_than_one_gpu_is_refused_with_a_message():
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_algorithmic_work_counts():
+    """The per-pass bytes and flops the roofline figures are priced with, re-counted key by key."""
+    sys.path.insert(0, ROOT)
+    import bench
+    import paper_2412_03594_amd as bllm
+    b = workload.with_prefix_prefill(workload.ragged_toy(3, dtype=workload.BF16, n_q_heads=8, n_kv_heads=2, head_dim=128,
+                                                         n_groups=3, max_prefix=90, max_group=4, max_suffix=40, max_chunk=20),
+                                     seed=3)
+    L = b.layer
+    pg = bllm.prefix_group_create((L.n_q_heads, L.n_kv_heads, L.head_dim, L.dtype), b.prefix_len, b.req_group,
+                                  b.req_suffix_len, b.req_q_len, host_only=True, prefix_q_len=b.prefix_q_len)
+    meta = pg.metadata()
+    w = bench.algorithmic_work(b, meta)
+    hq, hkv, d, e = L.n_q_heads, L.n_kv_heads, L.head_dim, 2
+    T = b.n_rows
+    # visible (query row, key) pairs of each part, counted one row at a time
+    pre_pairs = 0
+    for t in range(T):
+        r = meta["row_req"][t]
+        if r >= 0:
+            pre_pairs += int(b.prefix_len[b.req_group[r]])
+        else:
+            pre_pairs += int(meta["row_pos"][t]) + 1
+    suf_pairs = sum(int(meta["row_pos"][t]) + 1 for t in range(T) if meta["row_req"][t] >= 0)
+    assert w["prefix"]["flops"] == 4 * pre_pairs * hq * d
+    assert w["suffix"]["flops"] == 4 * suf_pairs * hq * d
+    used_groups = set(b.req_group[meta["row_req"][t]] for t in range(T) if meta["row_req"][t] >= 0) | \
+        {g for g in range(b.n_groups) if b.prefix_rows[g] > 0}
+    kv_prefix = 2 * sum(int(b.prefix_len[g]) for g in used_groups) * hkv * d * e
+    assert w["prefix"]["bytes"] == kv_prefix + T * hq * d * e + T * hq * (4 * d + 4)
+    kv_suffix = 2 * sum(int(s) for s, q in zip(b.req_suffix_len, b.req_q_len) if q > 0) * hkv * d * e
+    assert w["suffix"]["bytes"] == kv_suffix + T * hq * d * e + T * hq * (4 * d + 4)
+    assert w["merge"]["bytes"] == T * hq * (2 * (4 * d + 4) + e * d)
+    assert w["kv_append"]["bytes"] == T * (2 * 2 * hkv * d * e + 4)
+    pg.destroy()
