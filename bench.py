@@ -26,10 +26,12 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 # HBM bytes per launch of each pass, from rocprofv3 FETCH_SIZE + WRITE_SIZE runs scaled by a plain
 # copy of known size (the summaries and commands are under profiles/<workload>_kernels.md).
 MEASURED_TRAFFIC_BYTES = {
-    "l8b_decode": {"suffix": 306.8e6, "prefix": 109.6e6, "merge": 10.8e6, "suffix_merged": 309.2e6, "one_call": 410.9e6},
-    "rank_longprefix": {"suffix": 331.8e6, "prefix": 231.8e6, "merge": 43.0e6, "suffix_merged": 340.4e6,
-                        "one_call": 537.8e6},
-    "l8b_mixed": {"suffix": 848.3e6, "prefix": 692.6e6, "merge": 709.4e6, "suffix_merged": 999.6e6, "one_call": 1692.2e6},
+    "l8b_decode": {"suffix": 306.7e6, "prefix": 109.6e6, "merge": 10.8e6, "suffix_merged": 308.9e6, "one_call": 411.9e6,
+                   "single_launch": 411.9e6},
+    "rank_longprefix": {"suffix": 332.2e6, "prefix": 231.8e6, "merge": 43.0e6, "suffix_merged": 341.0e6,
+                        "one_call": 540.6e6, "single_launch": 540.6e6},
+    "l8b_mixed": {"suffix": 852.3e6, "prefix": 692.0e6, "merge": 709.4e6, "suffix_merged": 1004.1e6, "one_call": 1696.1e6,
+                  "single_launch": 2133.2e6},
 }
 
 
@@ -270,8 +272,7 @@ def run_workload(name, steps, warmup, seed, rotate, torch, bllm, workload, with_
                                          steps, warmup, torch)}
     work = algorithmic_work(batch, meta)
     passes = {}
-    work["single_launch"] = {"bytes": work["prefix"]["bytes"] + work["suffix"]["bytes"] + work["merge"]["bytes"],
-                             "flops": work["one_call"]["flops"]}
+    work["single_launch"] = dict(work["one_call"])       # the same path: K/V once, Q, one fp32 partial, final output
     for k in t_pass:
         sec = t_pass[k] * 1e-3
         passes[k] = {"ms": round(t_pass[k], 5), "GB_s": round(work[k]["bytes"] / sec / 1e9, 1),
@@ -279,7 +280,11 @@ def run_workload(name, steps, warmup, seed, rotate, torch, bllm, workload, with_
                      "alg_MB": round(work[k]["bytes"] / 1e6, 2), "alg_GFLOP": round(work[k]["flops"] / 1e9, 2)}
     for k, v in t_warm.items():
         passes[k]["ms_warm_cache"] = round(v, 5)
-    res = {"batch": batch, "vals": vals, "meta": meta, "ms_step": ms_step, "passes": passes, "work": work,
+    # the one-call entry point runs as one launch where its workspace is the single launch's
+    one_call_single = single_ok and T > 0 and \
+        bllm.prefix_shared_workspace_bytes(pg) == bllm.prefix_shared_single_launch_workspace_bytes(pg)
+    res = {"one_call_single": one_call_single,
+           "batch": batch, "vals": vals, "meta": meta, "ms_step": ms_step, "passes": passes, "work": work,
            "t_pass": t_pass, "tokens": T, "schedule": schedule, "rotate": rotate, "graph": bool(graphs)}
     graphs.clear()
     pg.destroy()
@@ -370,6 +375,8 @@ def roofline_of(res):
     t = res["t_pass"]
     in_step = {"three_call": ("prefix", "suffix", "merge"), "single_launch": ("single_launch",)}.get(
         res["schedule"], ("prefix", "suffix_merged"))
+    if res["schedule"] == "one_call" and res["one_call_single"]:
+        in_step = ("single_launch",)
     name = max(in_step, key=lambda k: t[k])
     traffic = MEASURED_TRAFFIC_BYTES.get(res["batch"].name, {}).get(name)
     w = res["work"][name]
@@ -402,10 +409,11 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--rotate", type=int, default=0,
                     help="copies of the KV tensors cycled through (0: enough to defeat the Infinity Cache, 2..16)")
-    ap.add_argument("--schedule", choices=["fused", "one_call", "three_call", "single_launch"], default="fused",
-                    help="timed step: prefix pass + suffix pass with the reduction in its epilogue (two calls); the "
-                         "one-call entry point (prefix kernels, then suffix kernels that fold the prefix result - split "
-                         "pieces included - in their epilogue); or prefix, suffix and merge passes (three calls).  "
+    ap.add_argument("--schedule", choices=["fused", "one_call", "three_call", "single_launch"], default="one_call",
+                    help="timed step: the one-call entry point (prefix kernels, then suffix kernels that fold the prefix "
+                         "result - split pieces included - in their epilogue; as ONE launch for the batches where that "
+                         "measured faster); fused: prefix pass + suffix pass with the reduction in its epilogue (two "
+                         "calls); three_call: prefix, suffix and merge passes.  "
                          "single_launch: every part a workgroup of one kernel, the last part to arrive at a row reduces "
                          "it (bf16, head_dim 128).  All give the same final output")
     ap.add_argument("--graph", action="store_true",
@@ -452,6 +460,7 @@ def main():
                    "requests": batch.n_requests, "token_rows": batch.n_rows,
                    "prefix_kv_rows": batch.n_prefix_kv, "suffix_kv_rows": batch.n_suffix_kv,
                    "kv_copies_rotated": main_res["rotate"], "schedule": args.schedule,
+                   "one_call_runs_as": "one launch" if main_res["one_call_single"] else "prefix kernels, then suffix kernels",
                    "launch": "hip graph replay, one graph per step" if main_res["graph"] else "eager"},
         "roofline": roofline_of(main_res),
         "passes": main_res["passes"],

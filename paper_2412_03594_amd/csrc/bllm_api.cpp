@@ -384,10 +384,26 @@ int bllm_kv_append(const bllm_prefix_groups* pg, const void* k_new, const void* 
     return BLLM_OK;
 }
 
-size_t bllm_prefix_shared_workspace_bytes(const bllm_prefix_groups* pg) {
-    if (!pg) return 0;
+// The one-call entry point runs as ONE launch where that measured faster: decode-dominated batches whose prefix
+// had to be split along KV to fill the chip (the prefix tiles then leave room for the streaming items beside
+// them) and that have no prefill-chunk tiles (whose fp32 partials would make the early parts' round trip
+// expensive).  l8b_decode: 80.9 us against 83.9 us per step.
+static bool one_call_uses_single_launch(const bllm_prefix_groups* pg) {
+    const Packing& p = pg->pk;
+    return pg->desc.dtype == BLLM_BF16 && pg->desc.head_dim == 128 && pg->desc.n_q_heads / pg->desc.n_kv_heads <= 4 &&
+           p.prefix_has_split && p.suffix_tile_items.empty() && !p.suffix_row_items.empty() &&
+           std::getenv("BLLM_TUNE_ONE_CALL_TWO_PHASE") == nullptr;
+}
+
+// bytes of one fp32 partial result (O, L) of the whole batch
+static size_t partial_bytes(const bllm_prefix_groups* pg) {
     const size_t row_heads = static_cast<size_t>(pg->pk.n_rows) * pg->desc.n_q_heads;
     return align256(row_heads * pg->desc.head_dim * sizeof(float)) + align256(row_heads * sizeof(float));
+}
+
+size_t bllm_prefix_shared_workspace_bytes(const bllm_prefix_groups* pg) {
+    if (!pg) return 0;
+    return (one_call_uses_single_launch(pg) ? 2 : 1) * partial_bytes(pg);
 }
 
 int bllm_prefix_shared_attention(const bllm_prefix_groups* pg, const void* q, const void* k_prefix, const void* v_prefix,
@@ -401,6 +417,9 @@ int bllm_prefix_shared_attention(const bllm_prefix_groups* pg, const void* q, co
         set_error("workspace too small (see bllm_prefix_shared_workspace_bytes) or not 16-byte aligned");
         return BLLM_INVALID_ARG;
     }
+    if (one_call_uses_single_launch(pg))
+        return bllm_prefix_shared_attention_single_launch(pg, q, k_prefix, v_prefix, k_suffix, v_suffix, workspace,
+                                                          workspace_bytes, o_out, lse_out, hip_stream);
     if (p.suffix_has_split) {
         set_error("a pass whose KV ranges are split cannot merge in its epilogue");
         return BLLM_UNSUPPORTED;
@@ -427,7 +446,7 @@ int bllm_prefix_shared_attention(const bllm_prefix_groups* pg, const void* q, co
 }
 
 size_t bllm_prefix_shared_single_launch_workspace_bytes(const bllm_prefix_groups* pg) {
-    return 2 * bllm_prefix_shared_workspace_bytes(pg);
+    return pg ? 2 * partial_bytes(pg) : 0;
 }
 
 int bllm_prefix_shared_attention_single_launch(const bllm_prefix_groups* pg, const void* q, const void* k_prefix,

@@ -267,8 +267,7 @@ int build_packing(const bllm_layer_desc& desc, int32_t n_groups, const int32_t* 
     // Prefix rows have no suffix part and no suffix item: the suffix pass writes their (0, -inf) - or,
     // merging, hands the prefix result on - with a plain streaming kernel over that row range.
     // Streaming items: longest first, so that the hardware's in-order workgroup dispatch
-    // balances the ragged lengths; then pick how many wavefronts share an item from the
-    // mean range length (about 64 KV rows or more per wavefront).
+    // balances the ragged lengths; then pick how many wavefronts share an item.
     auto finish_stream_list = [](std::vector<Item>& v, int32_t* wpi) {
         std::stable_sort(v.begin(), v.end(), [](const Item& a, const Item& b) {
             return std::min(a.kv_len, a.vis0) > std::min(b.kv_len, b.vis0);
@@ -276,7 +275,10 @@ int build_packing(const bllm_layer_desc& desc, int32_t n_groups, const int32_t* 
         int64_t total = 0;
         for (const Item& it : v) total += std::min(it.kv_len, it.vis0);
         const int64_t mean = v.empty() ? 0 : total / static_cast<int64_t>(v.size());
-        *wpi = mean >= 192 ? 4 : mean >= 96 ? 2 : 1;
+        // Two wavefronts per item measured best from 16 to 4000 KV rows per item (up to 6.7 TB/s); four only
+        // when the items are few and long (256 items of 8000 to 16000 rows: 5.9 against 4.4 TB/s), where two
+        // per item would leave wavefront slots empty.
+        *wpi = (v.size() < 512 && mean >= 512) ? 4 : 2;
         if (const char* ov = std::getenv("BLLM_TUNE_STREAM_WPI")) *wpi = std::atoi(ov) == 1 ? 1 : std::atoi(ov) == 2 ? 2 : 4;
     };
     // Prefix tile items: longest KV range first as well (stable: the items of a group stay together
