@@ -385,14 +385,16 @@ int bllm_kv_append(const bllm_prefix_groups* pg, const void* k_new, const void* 
 }
 
 // The one-call entry point runs as ONE launch where that measured faster: decode-dominated batches whose prefix
-// had to be split along KV to fill the chip (the prefix tiles then leave room for the streaming items beside
-// them) and that have no prefill-chunk tiles (whose fp32 partials would make the early parts' round trip
-// expensive).  l8b_decode: 80.9 us against 83.9 us per step.
+// had to be split along KV to fill the chip, with at most one prefix tile per compute unit (so that a streaming
+// workgroup fits beside it), enough streaming items to fill the rest of the chip while the tiles run, and no
+// prefill-chunk tiles (whose fp32 partials would make the early parts' round trip expensive).
+// l8b_decode: 80.2 us against 83.9 us per step; 256 decode rows on one 2048-token prefix: 72.7 against 77.6 us.
+// Measured the other way: 32 decode rows on one prefix (41 against 27 us), 512 prefix tiles (220 against 217 us).
 static bool one_call_uses_single_launch(const bllm_prefix_groups* pg) {
     const Packing& p = pg->pk;
     return pg->desc.dtype == BLLM_BF16 && pg->desc.head_dim == 128 && pg->desc.n_q_heads / pg->desc.n_kv_heads <= 4 &&
-           p.prefix_has_split && p.suffix_tile_items.empty() && !p.suffix_row_items.empty() &&
-           std::getenv("BLLM_TUNE_ONE_CALL_TWO_PHASE") == nullptr;
+           p.prefix_has_split && p.prefix_tile_items.size() <= 256 && p.suffix_tile_items.empty() &&
+           p.suffix_row_items.size() >= 1024 && std::getenv("BLLM_TUNE_ONE_CALL_TWO_PHASE") == nullptr;
 }
 
 // bytes of one fp32 partial result (O, L) of the whole batch
