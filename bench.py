@@ -277,7 +277,9 @@ def run_workload(name, steps, warmup, seed, rotate, torch, bllm, workload, with_
         sec = t_pass[k] * 1e-3
         passes[k] = {"ms": round(t_pass[k], 5), "GB_s": round(work[k]["bytes"] / sec / 1e9, 1),
                      "TFLOP_s": round(work[k]["flops"] / sec / 1e12, 2),
-                     "alg_MB": round(work[k]["bytes"] / 1e6, 2), "alg_GFLOP": round(work[k]["flops"] / 1e9, 2)}
+                     "alg_MB": round(work[k]["bytes"] / 1e6, 2), "alg_GFLOP": round(work[k]["flops"] / 1e9, 2),
+                     "frac_hbm_peak": round(work[k]["bytes"] / sec / 1e9 / PEAK_HBM_GBS, 4),
+                     "frac_mfma_peak": round(work[k]["flops"] / sec / 1e12 / PEAK_BF16_TFLOPS, 4)}
     for k, v in t_warm.items():
         passes[k]["ms_warm_cache"] = round(v, 5)
     # the one-call entry point runs as one launch where its workspace is the single launch's
