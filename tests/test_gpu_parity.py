@@ -446,3 +446,44 @@ def test_kv_append_leaves_other_rows_alone_and_validates():
     with pytest.raises(bllm.BllmError):
         bllm.kv_append(pg, None, v_new.to(dev), kp, vp, ks, vs)
     pg.destroy()
+
+
+def test_single_launch_repeated_calls_agree_with_two_calls():
+    """The single launch 90 times in a row on the headline decode batch, three KV sets in turn: which part
+    reduces a row depends on timing, the result must not (beyond the output's rounding)."""
+    import torch
+    import paper_2412_03594_amd as bllm
+    b = workload.l8b_decode(0)
+    L = b.layer
+    dev = torch.device("cuda:0")
+    pg = bllm.prefix_group_create(layer_tuple(L), b.prefix_len, b.req_group, b.req_suffix_len, b.req_q_len)
+    T = pg.metadata()["n_rows"]
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(1)
+    mk = lambda n, h: torch.randn((n, h, L.head_dim), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    q = mk(T, L.n_q_heads)
+    kv = [[mk(b.n_prefix_kv, L.n_kv_heads), mk(b.n_prefix_kv, L.n_kv_heads), mk(b.n_suffix_kv, L.n_kv_heads),
+           mk(b.n_suffix_kv, L.n_kv_heads)] for _ in range(3)]
+    ws = torch.empty(bllm.prefix_shared_single_launch_workspace_bytes(pg) // 4 + 64, device=dev, dtype=torch.float32)
+    o1 = torch.empty((T, L.n_q_heads, L.head_dim), device=dev)
+    l1 = torch.empty((T, L.n_q_heads), device=dev)
+    new_out = lambda: (torch.zeros((T, L.n_q_heads, L.head_dim), device=dev, dtype=torch.bfloat16),
+                       torch.zeros((T, L.n_q_heads), device=dev))
+    refs = []
+    for k in kv:
+        o, l = new_out()
+        bllm.shared_prefix_attention(pg, q, k[0], k[1], o1, l1)
+        bllm.suffix_attention_merged(pg, q, k[2], k[3], o1, l1, o, l)
+        refs.append((o.float(), l))
+    outs = [new_out() for _ in range(3)]
+    for i in range(90):
+        j = i % 3
+        bllm.prefix_shared_attention_single_launch(pg, q, kv[j][0], kv[j][1], kv[j][2], kv[j][3], ws, outs[j][0], outs[j][1])
+        if j == 2:
+            torch.cuda.synchronize()
+            for (o, l), (ro, rl) in zip(outs, refs):
+                assert (o.float() - ro).abs().max().item() <= 2e-2
+                assert (l - rl).abs().max().item() <= 1e-5
+                o.zero_()
+                l.zero_()
+    pg.destroy()
