@@ -212,3 +212,29 @@ def test_work_items_cover_every_row_head_once():
             assert min(it[4], it[5] + i) == m["row_pos"][t] + 1
             seen[t, it[2]] += 1
     assert np.all(seen == 1)
+
+
+def test_one_call_workspace_tells_which_form_runs():
+    """The one-call entry point runs decode-dominated batches with a split prefix as one launch (its workspace
+    is then the single launch's: two partial results), everything else as prefix kernels followed by suffix
+    kernels (one partial result)."""
+    expect_one_launch = {"l8b_decode": True, "rank_longprefix": False, "l8b_mixed": False, "l8b_decode_prefill": False,
+                         "l70b_zipf_32k": False, "tiny_fp32": False}
+    for name, one_launch in expect_one_launch.items():
+        b = workload.CONFIGS[name](0)
+        pg = host_pack(b)
+        one = bllm.prefix_shared_workspace_bytes(pg)
+        both = bllm.prefix_shared_single_launch_workspace_bytes(pg)
+        L = b.layer
+        partial = -(-b.n_rows * L.n_q_heads * L.head_dim * 4 // 256) * 256 + -(-b.n_rows * L.n_q_heads * 4 // 256) * 256
+        assert both == 2 * partial, name
+        assert one == (both if one_launch else partial), name
+        pg.destroy()
+    b = workload.kernel_bench_shape(2048, 256, 256)
+    pg = host_pack(b)
+    assert bllm.prefix_shared_workspace_bytes(pg) == bllm.prefix_shared_single_launch_workspace_bytes(pg)
+    pg.destroy()
+    b = workload.kernel_bench_shape(2048, 256, 32)            # too few streaming items to fill the chip
+    pg = host_pack(b)
+    assert 2 * bllm.prefix_shared_workspace_bytes(pg) == bllm.prefix_shared_single_launch_workspace_bytes(pg)
+    pg.destroy()
