@@ -92,12 +92,13 @@ int upload(bllm_prefix_groups* pg, hipStream_t stream) {
     hipError_t e = hipGetDevice(&pg->device);
     if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
     const size_t row_elems = static_cast<size_t>(pg->desc.n_q_heads) * pg->desc.head_dim;
-    const size_t ws_rows = static_cast<size_t>(std::max(p.n_prefix_ws_rows, p.n_suffix_ws_rows));
-    const size_t sizes[10] = {bytes_of(p.prefix_tile_items), bytes_of(p.prefix_row_items), bytes_of(p.suffix_tile_items),
+    const size_t ws_rows = static_cast<size_t>(std::max({p.n_prefix_ws_rows, p.n_suffix_ws_rows, p.n_sl_prefix_ws_rows}));
+    const size_t sizes[12] = {bytes_of(p.prefix_tile_items), bytes_of(p.prefix_row_items), bytes_of(p.suffix_tile_items),
                              bytes_of(p.suffix_row_items),  bytes_of(p.prefix_row_split), bytes_of(p.suffix_row_split),
                              align256(ws_rows * row_elems * sizeof(float)),
                              align256(ws_rows * pg->desc.n_q_heads * sizeof(float)), bytes_of(p.row_kv_dst),
-                             align256(static_cast<size_t>(p.n_rows) * pg->desc.n_kv_heads * sizeof(int32_t))};
+                             align256(static_cast<size_t>(p.n_rows) * pg->desc.n_kv_heads * sizeof(int32_t)),
+                             bytes_of(p.sl_prefix_tile_items), bytes_of(p.sl_prefix_row_split)};
     size_t total = 256;
     for (size_t s : sizes) total += s;
     e = hipMalloc(&pg->dev_blob, total);
@@ -119,6 +120,8 @@ int upload(bllm_prefix_groups* pg, hipStream_t stream) {
     pg->d.ws_lse = reinterpret_cast<float*>(place(sizes[7]));
     pg->d.row_kv_dst = reinterpret_cast<int32_t*>(place(sizes[8]));
     pg->d.arrivals = reinterpret_cast<int32_t*>(place(sizes[9]));
+    pg->d.sl_prefix_tile_items = reinterpret_cast<Item*>(place(sizes[10]));
+    pg->d.sl_prefix_row_split = reinterpret_cast<RowSplit*>(place(sizes[11]));
     e = hipMemsetAsync(pg->d.arrivals, 0, sizes[9], stream);      // at create only; the kernels keep them at zero
     if (e != hipSuccess) return hip_fail(e, "hipMemsetAsync(arrival counters)");
 
@@ -138,6 +141,8 @@ int upload(bllm_prefix_groups* pg, hipStream_t stream) {
     BLLM_UP(pg->d.prefix_row_split, p.prefix_row_split);
     BLLM_UP(pg->d.suffix_row_split, p.suffix_row_split);
     BLLM_UP(pg->d.row_kv_dst, p.row_kv_dst);
+    BLLM_UP(pg->d.sl_prefix_tile_items, p.sl_prefix_tile_items);
+    BLLM_UP(pg->d.sl_prefix_row_split, p.sl_prefix_row_split);
 #undef BLLM_UP
     // The source vectors are pageable, so the copies above are staged; the
     // synchronisation makes the handle usable from any stream afterwards.
@@ -392,9 +397,7 @@ int bllm_kv_append(const bllm_prefix_groups* pg, const void* k_new, const void* 
 // Measured the other way: 32 decode rows on one prefix (41 against 27 us), 512 prefix tiles (220 against 217 us).
 static bool one_call_uses_single_launch(const bllm_prefix_groups* pg) {
     const Packing& p = pg->pk;
-    return pg->desc.dtype == BLLM_BF16 && pg->desc.head_dim == 128 && pg->desc.n_q_heads / pg->desc.n_kv_heads <= 4 &&
-           p.prefix_has_split && p.prefix_tile_items.size() <= 256 && p.suffix_tile_items.empty() &&
-           p.suffix_row_items.size() >= 1024 && std::getenv("BLLM_TUNE_ONE_CALL_TWO_PHASE") == nullptr;
+    return p.single_launch && std::getenv("BLLM_TUNE_ONE_CALL_TWO_PHASE") == nullptr;
 }
 
 // bytes of one fp32 partial result (O, L) of the whole batch
@@ -482,14 +485,15 @@ int bllm_prefix_shared_attention_single_launch(const bllm_prefix_groups* pg, con
     float* o2 = reinterpret_cast<float*>(w + o_bytes + l_bytes);
     float* l2 = reinterpret_cast<float*>(w + 2 * o_bytes + l_bytes);
     HFusedLists lists;
-    lists.prefix_tiles = pg->d.prefix_tile_items;
+    // a batch that qualifies for this form has its own list of prefix tiles (fewer, longer pieces)
+    lists.prefix_tiles = p.single_launch ? pg->d.sl_prefix_tile_items : pg->d.prefix_tile_items;
     lists.suffix_tiles = pg->d.suffix_tile_items;
     lists.suffix_rows = pg->d.suffix_row_items;
-    lists.n_prefix_tiles = static_cast<int32_t>(p.prefix_tile_items.size());
+    lists.n_prefix_tiles = static_cast<int32_t>(p.single_launch ? p.sl_prefix_tile_items.size() : p.prefix_tile_items.size());
     lists.n_suffix_tiles = static_cast<int32_t>(p.suffix_tile_items.size());
     lists.n_suffix_rows = static_cast<int32_t>(p.suffix_row_items.size());
     lists.n_request_rows = p.group_prefix_row_start[0];
-    lists.prefix_row_split = pg->d.prefix_row_split;
+    lists.prefix_row_split = p.single_launch ? pg->d.sl_prefix_row_split : pg->d.prefix_row_split;
     lists.ws_o = pg->d.ws_o;
     lists.ws_lse = pg->d.ws_lse;
     lists.arrivals = pg->d.arrivals;

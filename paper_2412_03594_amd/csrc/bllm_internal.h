@@ -41,6 +41,11 @@ struct Packing {
     int32_t tile_rows = 0, prefix_split_len = 0, suffix_split_len = 0;
     int32_t n_prefix_ws_rows = 0, n_suffix_ws_rows = 0;
     bool prefix_has_split = false, suffix_has_split = false;
+    // prefix tiles of the single-launch form (fewer, longer pieces), when the batch qualifies for it
+    bool single_launch = false, sl_prefix_has_split = false;
+    std::vector<Item> sl_prefix_tile_items;
+    std::vector<RowSplit> sl_prefix_row_split;
+    int32_t n_sl_prefix_ws_rows = 0;
     // wavefronts that share one streaming item (1, 2 or 4), per pass
     int32_t prefix_stream_wpi = 4, suffix_stream_wpi = 4;
     // wavefronts per MFMA tile workgroup (32 stacked query rows each): tile_rows = 32 * tile_waves / rho
@@ -56,6 +61,8 @@ struct DeviceLists {
     RowSplit* suffix_row_split = nullptr;
     int32_t* row_kv_dst = nullptr;
     int32_t* arrivals = nullptr;   // [n_rows, Hkv] arrival counters of the single-launch path, zero between calls
+    Item* sl_prefix_tile_items = nullptr;
+    RowSplit* sl_prefix_row_split = nullptr;
     float* ws_o = nullptr;     // [ws_rows, Hq, D]
     float* ws_lse = nullptr;   // [ws_rows, Hq]
 };

@@ -17,6 +17,8 @@ constexpr int kRowsPerWave = 32;         // stacked query rows (token rows x hea
 constexpr int kKvTile = 64;             // KV rows per MFMA inner step; split lengths are multiples of it
 constexpr int kSplitWhenBelow = 512;    // split the prefix when fewer tile items than this exist
 constexpr int kSplitTargetItems = 512;  // two workgroups per compute unit
+constexpr int kSingleLaunchSplitBelow = 128;   // the single launch splits prefixes when fewer tiles than this exist ...
+constexpr int kSingleLaunchTargetItems = 128;  // ... into about half a tile per compute unit
 constexpr int kMinSplitLen = 512;       // shorter splits cost more in partial-result traffic than they gain
 
 bool fits_i32(int64_t v) { return v >= 0 && v <= std::numeric_limits<int32_t>::max(); }
@@ -161,9 +163,17 @@ int build_packing(const bllm_layer_desc& desc, int32_t n_groups, const int32_t* 
     p.prefix_row_split.assign(p.n_rows, RowSplit{0, 0, 0});
     p.suffix_row_split.assign(p.n_rows, RowSplit{0, 0, 0});
 
-    if (mfma) {
+    // Tile items of the shared-prefix part for a wanted number of tiles: prefixes are split along KV when the
+    // batch alone gives fewer tiles than `split_when_below`, into about `target_items` tiles.
+    struct PrefixTiles {
+        std::vector<Item>* items;
+        std::vector<RowSplit>* row_split;
+        int32_t* split_len;
+        int32_t* ws_rows;
+        bool* has_split;
+    };
+    auto build_prefix_tiles = [&](int split_when_below, int target_items, const PrefixTiles& out) -> int {
         const int32_t br = p.tile_rows;
-        // Split long prefixes when the batch alone cannot fill the chip.
         int64_t base_items = 0;
         int32_t max_lp = 0;
         for (int32_t g = 0; g < n_groups; ++g) {
@@ -173,13 +183,17 @@ int build_packing(const bllm_layer_desc& desc, int32_t n_groups, const int32_t* 
             base_items += static_cast<int64_t>(ceil_div(rows, br)) * n_kv_heads;
             max_lp = std::max(max_lp, prefix_len[g]);
         }
-        p.prefix_split_len = 0;
-        if (base_items > 0 && base_items < kSplitWhenBelow) {
-            const int32_t want = static_cast<int32_t>((kSplitTargetItems + base_items - 1) / base_items);
+        *out.split_len = 0;
+        if (base_items > 0 && base_items < split_when_below) {
+            const int32_t want = static_cast<int32_t>((target_items + base_items - 1) / base_items);
             int32_t len = ceil_div(ceil_div(max_lp, want), kKvTile) * kKvTile;
             len = std::max(len, kMinSplitLen);
-            if (len < max_lp) p.prefix_split_len = len;
+            if (len < max_lp) *out.split_len = len;
         }
+        const int32_t split_len = *out.split_len;
+        out.items->clear();
+        out.row_split->assign(p.n_rows, RowSplit{0, 0, 0});
+        *out.has_split = false;
         int64_t ws_rows = 0;
         for (int32_t g = 0; g < n_groups; ++g) {
             // Prefix rows: causal inside the prefix (row i sees the positions up to its own),
@@ -190,14 +204,13 @@ int build_packing(const bllm_layer_desc& desc, int32_t n_groups, const int32_t* 
                 const int32_t n = std::min(br, n_pre - i0);
                 const int32_t first_vis = prefix_len[g] - n_pre + i0 + 1;
                 for (int32_t j = 0; j < n_kv_heads; ++j)
-                    p.prefix_tile_items.push_back(
-                        Item{prow0 + i0, n, j, p.prefix_kv_start[g], first_vis + n - 1, first_vis, -1, 0});
+                    out.items->push_back(Item{prow0 + i0, n, j, p.prefix_kv_start[g], first_vis + n - 1, first_vis, -1, 0});
             }
             const int32_t row0 = p.group_row_start[g];
             const int32_t rows = p.group_row_start[g + 1] - row0;
             if (rows == 0) continue;
             const int32_t lp = prefix_len[g];
-            const int32_t n_sp = (p.prefix_split_len > 0 && lp > p.prefix_split_len) ? ceil_div(lp, p.prefix_split_len) : 1;
+            const int32_t n_sp = (split_len > 0 && lp > split_len) ? ceil_div(lp, split_len) : 1;
             const int32_t ws_base = static_cast<int32_t>(ws_rows);
             if (n_sp > 1) {
                 ws_rows += static_cast<int64_t>(rows) * n_sp;
@@ -205,12 +218,12 @@ int build_packing(const bllm_layer_desc& desc, int32_t n_groups, const int32_t* 
                     set_error("prefix split workspace overflows int32 rows");
                     return BLLM_INVALID_ARG;
                 }
-                for (int32_t i = 0; i < rows; ++i) p.prefix_row_split[row0 + i] = RowSplit{ws_base + i, rows, n_sp};
-                p.prefix_has_split = true;
+                for (int32_t i = 0; i < rows; ++i) (*out.row_split)[row0 + i] = RowSplit{ws_base + i, rows, n_sp};
+                *out.has_split = true;
             }
             for (int32_t c = 0; c < n_sp; ++c) {
-                const int32_t kv_off = (n_sp > 1) ? c * p.prefix_split_len : 0;
-                const int32_t kv_len = (n_sp > 1) ? std::min(p.prefix_split_len, lp - kv_off) : lp;
+                const int32_t kv_off = (n_sp > 1) ? c * split_len : 0;
+                const int32_t kv_len = (n_sp > 1) ? std::min(split_len, lp - kv_off) : lp;
                 for (int32_t i0 = 0; i0 < rows; i0 += br) {
                     for (int32_t j = 0; j < n_kv_heads; ++j) {
                         Item it;
@@ -222,12 +235,25 @@ int build_packing(const bllm_layer_desc& desc, int32_t n_groups, const int32_t* 
                         it.vis0 = kv_len;
                         it.dst_row = (n_sp > 1) ? ws_base + c * rows + i0 : -1;
                         it.reserved = 0;
-                        p.prefix_tile_items.push_back(it);
+                        out.items->push_back(it);
                     }
                 }
             }
         }
-        p.n_prefix_ws_rows = static_cast<int32_t>(ws_rows);
+        *out.ws_rows = static_cast<int32_t>(ws_rows);
+        // longest KV range first (stable: the items of a group stay together and keep sharing its K/V in
+        // L2, the KV heads of one row block stay adjacent)
+        std::stable_sort(out.items->begin(), out.items->end(), [](const Item& a, const Item& b) { return a.kv_len > b.kv_len; });
+        return BLLM_OK;
+    };
+
+    if (mfma) {
+        const int32_t br = p.tile_rows;
+        // Split long prefixes when the batch alone cannot fill the chip.
+        const int rc = build_prefix_tiles(kSplitWhenBelow, kSplitTargetItems,
+                                          PrefixTiles{&p.prefix_tile_items, &p.prefix_row_split, &p.prefix_split_len,
+                                                      &p.n_prefix_ws_rows, &p.prefix_has_split});
+        if (rc != BLLM_OK) return rc;
 
         for (int32_t a = 0; a < p.n_active; ++a) {
             const int32_t r = p.perm_req[a];
@@ -281,14 +307,28 @@ int build_packing(const bllm_layer_desc& desc, int32_t n_groups, const int32_t* 
         *wpi = (v.size() < 512 && mean >= 512) ? 4 : 2;
         if (const char* ov = std::getenv("BLLM_TUNE_STREAM_WPI")) *wpi = std::atoi(ov) == 1 ? 1 : std::atoi(ov) == 2 ? 2 : 4;
     };
-    // Prefix tile items: longest KV range first as well (stable: the items of a group stay together
-    // and keep sharing its K/V in L2, the KV heads of one row block stay adjacent).  The chunk
-    // items of the suffix pass keep their request order, which measured faster (K/V reuse between
-    // the row blocks of one request).
-    std::stable_sort(p.prefix_tile_items.begin(), p.prefix_tile_items.end(),
-                     [](const Item& a, const Item& b) { return a.kv_len > b.kv_len; });
+    // The chunk items of the suffix pass keep their request order, which measured faster than longest
+    // first (K/V reuse between the row blocks of one request).
     finish_stream_list(p.prefix_row_items, &p.prefix_stream_wpi);
     finish_stream_list(p.suffix_row_items, &p.suffix_stream_wpi);
+    // A second list of prefix tiles for the whole path as ONE launch (decode-dominated batches: no prefill
+    // chunks, enough streaming items to fill the chip beside the tiles, up to 4 query heads per KV head).
+    // There the tiles share the compute units with the streaming items from the start, and half a tile per
+    // compute unit measured best (l8b_decode: 2 pieces 74.8 us, 3 pieces 75.9, 4 pieces 77.8, unsplit 98.9).
+    p.single_launch = false;
+    if (mfma && rho <= 4 && p.suffix_tile_items.empty() && p.suffix_row_items.size() >= 1024) {
+        int32_t split_len = 0;
+        const int rc = build_prefix_tiles(kSingleLaunchSplitBelow, kSingleLaunchTargetItems,
+                                          PrefixTiles{&p.sl_prefix_tile_items, &p.sl_prefix_row_split, &split_len,
+                                                      &p.n_sl_prefix_ws_rows, &p.sl_prefix_has_split});
+        if (rc != BLLM_OK) return rc;
+        p.single_launch = p.sl_prefix_has_split && p.sl_prefix_tile_items.size() <= 256;
+        if (!p.single_launch) {
+            p.sl_prefix_tile_items.clear();
+            p.sl_prefix_row_split.clear();
+            p.n_sl_prefix_ws_rows = 0;
+        }
+    }
     return BLLM_OK;
 }
 
