@@ -26,8 +26,8 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 # HBM bytes per launch of each pass, from rocprofv3 FETCH_SIZE + WRITE_SIZE runs scaled by a plain
 # copy of known size (the summaries and commands are under profiles/<workload>_kernels.md).
 MEASURED_TRAFFIC_BYTES = {
-    "l8b_decode": {"suffix": 306.7e6, "prefix": 109.6e6, "merge": 10.8e6, "suffix_merged": 308.9e6, "one_call": 411.9e6,
-                   "single_launch": 411.9e6},
+    "l8b_decode": {"suffix": 306.7e6, "prefix": 109.6e6, "merge": 10.8e6, "suffix_merged": 308.9e6, "one_call": 398.4e6,
+                   "single_launch": 398.4e6},
     "rank_longprefix": {"suffix": 332.2e6, "prefix": 231.8e6, "merge": 43.0e6, "suffix_merged": 341.0e6,
                         "one_call": 540.6e6, "single_launch": 540.6e6},
     "l8b_mixed": {"suffix": 852.3e6, "prefix": 692.0e6, "merge": 709.4e6, "suffix_merged": 1004.1e6, "one_call": 1696.1e6,
