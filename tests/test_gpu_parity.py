@@ -487,3 +487,19 @@ def test_single_launch_repeated_calls_agree_with_two_calls():
                 o.zero_()
                 l.zero_()
     pg.destroy()
+
+
+@pytest.mark.parametrize("seed", range(100, 124))
+def test_random_batches_all_forms(seed):
+    """Seeded random ragged batches over head ratios, head dims, dtypes, group counts and length scales, every
+    third with prefix-prefill rows, every second through the KV append: every call form against the oracle."""
+    combos = [(8, 2, 128, workload.BF16), (8, 1, 128, workload.BF16), (4, 4, 128, workload.BF16),
+              (16, 8, 128, workload.BF16), (8, 2, 64, workload.BF16), (4, 2, 64, workload.F32), (8, 2, 128, workload.F32)]
+    hq, hkv, d, dt = combos[seed % len(combos)]
+    rng = np.random.default_rng(seed)
+    b = workload.ragged_toy(seed, dtype=dt, n_q_heads=hq, n_kv_heads=hkv, head_dim=d, n_groups=int(rng.integers(1, 6)),
+                            max_prefix=int(rng.choice([40, 300, 1300])), max_group=int(rng.integers(1, 9)),
+                            max_suffix=int(rng.choice([30, 200, 700])), max_chunk=int(rng.choice([10, 90, 300])))
+    if seed % 3 == 0:
+        b = workload.with_prefix_prefill(b, seed=seed, max_rows=int(rng.choice([50, 400])) if seed % 2 else None)
+    check_all(b, workload.draw_values(b), append=(seed % 2 == 0))
