@@ -153,6 +153,9 @@ __device__ __forceinline__ void tile_attention_body(
         store_out4<true>(mt.o_out, rh * kD + x, r.x, r.y, r.z, r.w);
         return lse;
     };
+    // The first other partial's log-sum-exp is requested now, so the epilogue finds it there.
+    float first_other_l = -INFINITY;
+    if (mt.o_a != nullptr && row_ok && kv_len > 0) first_other_l = other_l(0);
     if (kv_len <= 0 && mt.o_a != nullptr) {      // empty part, fused merge: the other part passes through
         if (row_ok) {
             float lse = -INFINITY;
@@ -387,13 +390,23 @@ __device__ __forceinline__ void tile_attention_body(
         // Fused merge: this part is (O / l, log-sum-exp lb), the other part comes from memory.  The
         // weights of all parts (relative to their common maximum) come first, then every partial
         // is added with its 16 row pieces fetched at once.
+        // The rows of the first other partial are requested before anything waits for a log-sum-exp (an
+        // empty partial's rows are fetched but never used).
+        float4 xs0[16];
+        {
+            const float* src = other_o(0);
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) xs0[4 * db + i] = *reinterpret_cast<const float4*>(src + 32 * db + 8 * i + 4 * h);
+        }
         const float lb = (m_run + log2f(ltot)) * kLn2;          // finite: at least one key is visible
-        float top = lb;
-        for (int c = 0; c < n_other; ++c) top = fmaxf(top, other_l(c));
+        float top = fmaxf(lb, first_other_l);
+        for (int c = 1; c < n_other; ++c) top = fmaxf(top, other_l(c));
         const float w_own = expf(lb - top);
         float den = w_own;
         for (int c = 0; c < n_other; ++c) {
-            const float lc = other_l(c);
+            const float lc = c == 0 ? first_other_l : other_l(c);
             if (lc != -INFINITY) den += expf(lc - top);
         }
         const float inv_den = 1.f / den;
@@ -403,15 +416,20 @@ __device__ __forceinline__ void tile_attention_body(
 #pragma unroll
             for (int x = 0; x < 16; ++x) oacc[db][x] *= s_own;
         for (int c = 0; c < n_other; ++c) {
-            const float lc = other_l(c);
-            if (lc == -INFINITY) continue;                       // an empty partial's rows are never touched
+            const float lc = c == 0 ? first_other_l : other_l(c);
+            if (lc == -INFINITY) continue;                       // an empty partial's rows are never used
             const float wc = expf(lc - top) * inv_den;
-            const float* src = other_o(c);
             float4 xs[16];
+            if (c == 0) {
 #pragma unroll
-            for (int db = 0; db < 4; ++db)
+                for (int i = 0; i < 16; ++i) xs[i] = xs0[i];
+            } else {
+                const float* src = other_o(c);
 #pragma unroll
-                for (int i = 0; i < 4; ++i) xs[4 * db + i] = *reinterpret_cast<const float4*>(src + 32 * db + 8 * i + 4 * h);
+                for (int db = 0; db < 4; ++db)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) xs[4 * db + i] = *reinterpret_cast<const float4*>(src + 32 * db + 8 * i + 4 * h);
+            }
 #pragma unroll
             for (int db = 0; db < 4; ++db)
 #pragma unroll
