@@ -153,9 +153,6 @@ __device__ __forceinline__ void tile_attention_body(
         store_out4<true>(mt.o_out, rh * kD + x, r.x, r.y, r.z, r.w);
         return lse;
     };
-    // The first other partial's log-sum-exp is requested now, so the epilogue finds it there.
-    float first_other_l = -INFINITY;
-    if (mt.o_a != nullptr && row_ok && kv_len > 0) first_other_l = other_l(0);
     if (kv_len <= 0 && mt.o_a != nullptr) {      // empty part, fused merge: the other part passes through
         if (row_ok) {
             float lse = -INFINITY;
@@ -266,6 +263,10 @@ __device__ __forceinline__ void tile_attention_body(
     }
 
     dma_tile(0, smem_even);
+    // The first other partial's log-sum-exp is requested now, behind the first tile, so the epilogue finds
+    // it there.
+    float first_other_l = -INFINITY;
+    if (mt.o_a != nullptr && row_ok) first_other_l = other_l(0);
     wait_vector_memory<0>();
     __syncthreads();
 
