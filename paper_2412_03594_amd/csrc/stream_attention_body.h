@@ -140,7 +140,7 @@ __device__ __forceinline__ void stream_attention_body(
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wavefront-uniform: the item descriptor becomes a scalar load
     const int sub = lane & 15;
     const int item_in_block = wave / WPI;
     const int sw = wave % WPI;
