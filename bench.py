@@ -422,6 +422,9 @@ def main():
                     help="replay one captured HIP graph per timed step instead of launching eagerly (measured slower "
                          "than eager launches on the decode workload, faster on the long-running ones)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--device-values", action="store_true",
+                    help="draw the main workload's Q/K/V on the device (for the workloads whose KV takes minutes to "
+                         "draw on the host); implies --no-cpu-baseline, which needs the values on the host")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device-to-device copy (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -444,8 +447,10 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
 
+    if args.device_values:
+        args.no_cpu_baseline = True
     main_res = run_workload(args.workload, args.steps, args.warmup, args.seed, args.rotate, torch, bllm, workload,
-                            schedule=args.schedule, use_graph=args.graph)
+                            with_values_host=not args.device_values, schedule=args.schedule, use_graph=args.graph)
     batch = main_res["batch"]
     L = batch.layer
     out = {
