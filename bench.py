@@ -64,6 +64,10 @@ def algorithmic_work(batch, meta):
     suffix_merged = {"bytes": suffix["bytes"] + float(T * hq * d * e), "flops": suffix["flops"]}
     # the whole path in one call: the prefix partial is written once and read once
     one_call = {"bytes": prefix["bytes"] + suffix_merged["bytes"], "flops": prefix["flops"] + suffix["flops"]}
+    # rows of prefill chunks that one workgroup takes through both parts: no partial written or read, Q read once
+    pairs = meta.get("through_pair_items", np.zeros((0, 2, 8), np.int32))
+    t_through = float(pairs[pairs[:, 0, 2] == 0, 0, 1].sum()) if len(pairs) else 0.0
+    one_call["bytes"] -= t_through * hq * (2 * (4 * d + 4) + d * e)
     # the new K/V rows of the batch's own tokens: read once, written once, plus the destination index
     kv_append = {"bytes": float(T * (2 * 2 * hkv * d * e + 4)), "flops": 0.0}
     return {"prefix": prefix, "suffix": suffix, "merge": merge, "suffix_merged": suffix_merged, "one_call": one_call,

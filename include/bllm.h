@@ -99,6 +99,18 @@ typedef struct {
     int32_t n_suffix_ws_rows;          /* same for the suffix pass */
     const int32_t* prefix_row_split;   /* [T][3] per packed row: workspace row of split 0, stride between splits, number of splits (0 = written directly) */
     const int32_t* suffix_row_split;   /* [T][3] same for the suffix pass */
+    /* Lists of bllm_prefix_shared_attention for a batch with prefill chunks (BF16, D = 128; all empty / 0
+     * otherwise).  A request whose chunk fills its own tiles - q_len >= 2 and
+     * pad * prefix_len < 400 * q_len, pad = rows missing in its last tile - is taken through both parts in
+     * one workgroup (Sec. 4.3.3's two partial attentions reduced by the online softmax itself, Sec. 5): each
+     * of its (row block, KV head) tiles is a PAIR of items, the prefix range and then the request's own
+     * causal range, and no partial result exists for its rows.  The other rows keep the two-pass form, with
+     * the tiles below in place of prefix_tile_items / suffix_tile_items. */
+    int32_t n_through_pairs;              const int32_t* through_pair_items;        /* [n_through_pairs][2] items */
+    int32_t n_through_prefix_tile_items;  const int32_t* through_prefix_tile_items; /* shared-prefix tiles of the other rows */
+    int32_t n_through_suffix_tile_items;  const int32_t* through_suffix_tile_items; /* prefill-chunk tiles of the other requests */
+    int32_t n_through_prefix_ws_rows;     /* rows of split-partial workspace of through_prefix_tile_items */
+    const int32_t* through_prefix_row_split; /* [T][3] as prefix_row_split, for through_prefix_tile_items; null when n_through_pairs == 0 */
 } bllm_packing_view;
 
 #define BLLM_ITEM_INTS 8
@@ -255,7 +267,13 @@ int bllm_kv_append(const bllm_prefix_groups* pg, const void* k_new, const void* 
  * prefix result of every row into their own in their epilogue and write the
  * final output.  No separate reduction launch; a prefix that was split along
  * KV for occupancy is folded piece by piece, without a combine launch either.
- * The result equals the three-call sequence up to fp32 rounding.  For batches
+ * The result equals the three-call sequence up to fp32 rounding.  A request
+ * whose prefill chunk fills its own tiles (bf16, head_dim 128; the rule is at
+ * bllm_packing_view's through lists) is taken through both parts by one workgroup
+ * per (row block, KV head) inside the shared-prefix launch: the running softmax
+ * goes on from the prefix range into the request's own keys, which is the same
+ * reduction carried in registers, and no partial result of those rows is
+ * written or read.  For batches
  * where it measured faster (bf16, head_dim 128, up to 4 query heads per KV head, a
  * prefix that was split along KV to fill the chip into at most 256 tiles, at least
  * 1024 streaming items, decode rows only) the call

@@ -22,7 +22,10 @@ code so the two can be compared bit for bit:
     the prefix KV arrays (prefix_kv_start[group] + row_pos).
 
 build_work_lists re-derives, by the documented rules, the work lists the kernels
-consume (tile items, streaming items, split tables).  All arrays are int32.
+consume (tile items, streaming items, split tables), among them the lists of the
+one-call path for batches with prefill chunks: a request whose chunk fills its own
+tiles is taken through both parts of prefix-shared attention (Sec. 4.3.3) by one
+workgroup per (row block, KV head), as a pair of items.  All arrays are int32.
 """
 import numpy as np
 
@@ -117,6 +120,7 @@ SPLIT_WHEN_BELOW = 512      # split prefixes when fewer tile items than this wou
 SPLIT_TARGET_ITEMS = 512
 MIN_SPLIT_LEN = 512
 KV_TILE = 64
+THROUGH_GAIN = 400          # a chunk goes through both parts in one workgroup when pad * prefix_len < this * q_len
 
 
 def _ceil_div(a, b):
@@ -150,22 +154,44 @@ def build_work_lists(meta, prefix_len, req_suffix_len, req_q_len, n_q_heads, n_k
     suffix_row_split = [[0, 0, 0] for _ in range(T)]
     split_len = 0
     ws_rows = 0
-    if mfma:
+    th_pairs, th_prefix_tiles, th_suffix_tiles, th_row_split, th_ws_rows = [], [], [], None, 0
+    grq = [int(x) for x in meta["group_req_start"]]
+
+    def runs_of(g, skip):
+        """Runs (first packed row, rows) of group g's request rows, broken at the packed requests in skip."""
+        runs, cur = [], None
+        for a in range(grq[g], grq[g + 1]):
+            if a in skip:
+                if cur is not None:
+                    runs.append(cur)
+                cur = None
+            elif cur is None:
+                cur = [rrs[a], rrs[a + 1] - rrs[a]]
+            else:
+                cur[1] += rrs[a + 1] - rrs[a]
+        if cur is not None:
+            runs.append(cur)
+        return [r for r in runs if r[1] > 0]
+
+    def shared_prefix_tiles(skip, other_items):
+        """Tiles of the shared-prefix part over every request row not in `skip`, and over the prefix rows."""
         br = tile_rows
-        base_items, max_lp = 0, 0
+        tiles = []
+        row_split = [[0, 0, 0] for _ in range(T)]
+        base_items, max_lp, ln_split, n_ws = other_items, 0, 0, 0
         for g in range(G):
-            rows = grs[g + 1] - grs[g]
             base_items += _ceil_div(gprs[g + 1] - gprs[g], br) * n_kv_heads
-            if rows == 0 or prefix_len[g] == 0:
+            if prefix_len[g] == 0:
                 continue
-            base_items += _ceil_div(rows, br) * n_kv_heads
-            max_lp = max(max_lp, prefix_len[g])
+            for _, rows in runs_of(g, skip):
+                base_items += _ceil_div(rows, br) * n_kv_heads
+                max_lp = max(max_lp, prefix_len[g])
         if 0 < base_items < SPLIT_WHEN_BELOW:
             want = _ceil_div(SPLIT_TARGET_ITEMS, base_items)
             ln = _ceil_div(_ceil_div(max_lp, want), KV_TILE) * KV_TILE
             ln = max(ln, MIN_SPLIT_LEN)
             if ln < max_lp:
-                split_len = ln
+                ln_split = ln
         for g in range(G):
             # prefix rows: causal inside the prefix, never split, written directly
             n_pre = gprs[g + 1] - gprs[g]
@@ -173,35 +199,62 @@ def build_work_lists(meta, prefix_len, req_suffix_len, req_q_len, n_q_heads, n_k
                 n = min(br, n_pre - i0)
                 first_vis = prefix_len[g] - n_pre + i0 + 1
                 for j in range(n_kv_heads):
-                    prefix_tiles.append([gprs[g] + i0, n, j, pks[g], first_vis + n - 1, first_vis, -1, 0])
-            row0 = grs[g]
-            rows = grs[g + 1] - row0
-            if rows == 0:
-                continue
+                    tiles.append([gprs[g] + i0, n, j, pks[g], first_vis + n - 1, first_vis, -1, 0])
             lp = prefix_len[g]
-            n_sp = _ceil_div(lp, split_len) if (split_len > 0 and lp > split_len) else 1
-            ws_base = ws_rows
-            if n_sp > 1:
-                ws_rows += rows * n_sp
-                for i in range(rows):
-                    prefix_row_split[row0 + i] = [ws_base + i, rows, n_sp]
-            for c in range(n_sp):
-                kv_off = c * split_len if n_sp > 1 else 0
-                kv_len = min(split_len, lp - kv_off) if n_sp > 1 else lp
-                for i0 in range(0, rows, br):
-                    for j in range(n_kv_heads):
-                        prefix_tiles.append([row0 + i0, min(br, rows - i0), j, pks[g] + kv_off, kv_len, kv_len,
-                                             (ws_base + c * rows + i0) if n_sp > 1 else -1, 0])
-        for a, r in enumerate(perm):
+            for row0, rows in runs_of(g, skip):
+                n_sp = _ceil_div(lp, ln_split) if (ln_split > 0 and lp > ln_split) else 1
+                ws_base = n_ws
+                if n_sp > 1:
+                    n_ws += rows * n_sp
+                    for i in range(rows):
+                        row_split[row0 + i] = [ws_base + i, rows, n_sp]
+                for c in range(n_sp):
+                    kv_off = c * ln_split if n_sp > 1 else 0
+                    kv_len = min(ln_split, lp - kv_off) if n_sp > 1 else lp
+                    for i0 in range(0, rows, br):
+                        for j in range(n_kv_heads):
+                            tiles.append([row0 + i0, min(br, rows - i0), j, pks[g] + kv_off, kv_len, kv_len,
+                                          (ws_base + c * rows + i0) if n_sp > 1 else -1, 0])
+        # longest KV range first (stable)
+        tiles.sort(key=lambda it: -it[4])
+        return tiles, row_split, ln_split, n_ws
+
+    if mfma:
+        br = tile_rows
+        prefix_tiles, prefix_row_split, split_len, ws_rows = shared_prefix_tiles(set(), 0)
+
+        def chunk_tiles(a):
+            r = perm[a]
             nq, s, row0 = q_len[r], s_len[r], rrs[a]
-            if nq == 1:
+            return [[row0 + i0, min(br, nq - i0), j, rks[r], s - nq + i0 + min(br, nq - i0), s - nq + i0 + 1, -1, 0]
+                    for i0 in range(0, nq, br) for j in range(n_kv_heads)]
+
+        for a, r in enumerate(perm):
+            if q_len[r] == 1:
                 for j in range(n_kv_heads):
-                    suffix_rows.append([row0, 1, j, rks[r], s, s, -1, 0])
+                    suffix_rows.append([rrs[a], 1, j, rks[r], s_len[r], s_len[r], -1, 0])
             else:
-                for i0 in range(0, nq, br):
-                    n = min(br, nq - i0)
-                    for j in range(n_kv_heads):
-                        suffix_tiles.append([row0 + i0, n, j, rks[r], s - nq + i0 + n, s - nq + i0 + 1, -1, 0])
+                suffix_tiles += chunk_tiles(a)
+        # requests taken through both parts in one workgroup: the padding of their last row block over the
+        # prefix must cost less than the partial result they no longer write and read
+        group_of = {a: g for g in range(G) for a in range(grq[g], grq[g + 1])}
+        through = set()
+        for a, r in enumerate(perm):
+            nq = q_len[r]
+            pad = _ceil_div(nq, br) * br - nq
+            if nq >= 2 and pad * prefix_len[group_of[a]] < THROUGH_GAIN * nq:
+                through.add(a)
+        if through:
+            for a, r in enumerate(perm):
+                if q_len[r] < 2:
+                    continue
+                g = group_of[a]
+                for own in chunk_tiles(a):
+                    if a in through:
+                        th_pairs.append([[own[0], own[1], own[2], pks[g], prefix_len[g], prefix_len[g], -1, 0], own])
+                    else:
+                        th_suffix_tiles.append(own)
+            th_prefix_tiles, th_row_split, _, th_ws_rows = shared_prefix_tiles(through, len(th_pairs))
     else:
         for g in range(G):
             for t in range(grs[g], grs[g + 1]):
@@ -214,8 +267,7 @@ def build_work_lists(meta, prefix_len, req_suffix_len, req_q_len, n_q_heads, n_k
             for j in range(n_kv_heads):
                 suffix_rows.append([t, 1, j, rks[row_req[t]], row_pos[t] + 1, row_pos[t] + 1, -1, 0])
     # prefix rows have no suffix part and no suffix item
-    # prefix tile items: longest KV range first (stable); suffix tile items keep request order
-    prefix_tiles.sort(key=lambda it: -it[4])
+    # suffix tile items keep request order
     # streaming items: longest range first (stable)
     key = lambda it: -min(it[4], it[5])
     prefix_rows.sort(key=key)
@@ -228,4 +280,9 @@ def build_work_lists(meta, prefix_len, req_suffix_len, req_q_len, n_q_heads, n_k
         "prefix_row_split": arr(prefix_row_split, 3), "suffix_row_split": arr(suffix_row_split, 3),
         "prefix_split_len": split_len, "suffix_split_len": 0,
         "n_prefix_ws_rows": ws_rows, "n_suffix_ws_rows": 0,
+        "through_pair_items": np.asarray(th_pairs, dtype=np.int32).reshape(-1, 2, ITEM_INTS),
+        "through_prefix_tile_items": arr(th_prefix_tiles, ITEM_INTS),
+        "through_suffix_tile_items": arr(th_suffix_tiles, ITEM_INTS),
+        "through_prefix_row_split": arr(th_row_split if th_pairs else [], 3),
+        "n_through_prefix_ws_rows": th_ws_rows,
     }

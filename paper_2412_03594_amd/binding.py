@@ -46,7 +46,11 @@ class PackingView(C.Structure):
                 ("n_suffix_row_items", C.c_int32), ("suffix_row_items", _I32P),
                 ("tile_rows", C.c_int32), ("prefix_split_len", C.c_int32), ("suffix_split_len", C.c_int32),
                 ("n_prefix_ws_rows", C.c_int32), ("n_suffix_ws_rows", C.c_int32),
-                ("prefix_row_split", _I32P), ("suffix_row_split", _I32P)]
+                ("prefix_row_split", _I32P), ("suffix_row_split", _I32P),
+                ("n_through_pairs", C.c_int32), ("through_pair_items", _I32P),
+                ("n_through_prefix_tile_items", C.c_int32), ("through_prefix_tile_items", _I32P),
+                ("n_through_suffix_tile_items", C.c_int32), ("through_suffix_tile_items", _I32P),
+                ("n_through_prefix_ws_rows", C.c_int32), ("through_prefix_row_split", _I32P)]
 
 
 class BatchingParams(C.Structure):
@@ -185,6 +189,13 @@ class PrefixGroups:
         for name in ("prefix_tile_items", "prefix_row_items", "suffix_tile_items", "suffix_row_items"):
             n = getattr(v, "n_" + name)
             m[name] = arr(getattr(v, name), n * ITEM_INTS).reshape(n, ITEM_INTS)
+        n = v.n_through_pairs
+        m["through_pair_items"] = arr(v.through_pair_items, 2 * n * ITEM_INTS).reshape(n, 2, ITEM_INTS)
+        for name in ("through_prefix_tile_items", "through_suffix_tile_items"):
+            k = getattr(v, "n_" + name)
+            m[name] = arr(getattr(v, name), k * ITEM_INTS).reshape(k, ITEM_INTS)
+        m["n_through_prefix_ws_rows"] = v.n_through_prefix_ws_rows
+        m["through_prefix_row_split"] = arr(v.through_prefix_row_split, 3 * t if n > 0 else 0).reshape(-1, 3)
         self._meta = m
         return m
 

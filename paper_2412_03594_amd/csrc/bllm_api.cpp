@@ -92,13 +92,15 @@ int upload(bllm_prefix_groups* pg, hipStream_t stream) {
     hipError_t e = hipGetDevice(&pg->device);
     if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
     const size_t row_elems = static_cast<size_t>(pg->desc.n_q_heads) * pg->desc.head_dim;
-    const size_t ws_rows = static_cast<size_t>(std::max({p.n_prefix_ws_rows, p.n_suffix_ws_rows, p.n_sl_prefix_ws_rows}));
-    const size_t sizes[12] = {bytes_of(p.prefix_tile_items), bytes_of(p.prefix_row_items), bytes_of(p.suffix_tile_items),
+    const size_t ws_rows = static_cast<size_t>(std::max({p.n_prefix_ws_rows, p.n_suffix_ws_rows, p.n_sl_prefix_ws_rows, p.n_th_prefix_ws_rows}));
+    const size_t sizes[16] = {bytes_of(p.prefix_tile_items), bytes_of(p.prefix_row_items), bytes_of(p.suffix_tile_items),
                              bytes_of(p.suffix_row_items),  bytes_of(p.prefix_row_split), bytes_of(p.suffix_row_split),
                              align256(ws_rows * row_elems * sizeof(float)),
                              align256(ws_rows * pg->desc.n_q_heads * sizeof(float)), bytes_of(p.row_kv_dst),
                              align256(static_cast<size_t>(p.n_rows) * pg->desc.n_kv_heads * sizeof(int32_t)),
-                             bytes_of(p.sl_prefix_tile_items), bytes_of(p.sl_prefix_row_split)};
+                             bytes_of(p.sl_prefix_tile_items), bytes_of(p.sl_prefix_row_split),
+                             bytes_of(p.th_pair_items), bytes_of(p.th_prefix_tile_items), bytes_of(p.th_suffix_tile_items),
+                             bytes_of(p.th_prefix_row_split)};
     size_t total = 256;
     for (size_t s : sizes) total += s;
     e = hipMalloc(&pg->dev_blob, total);
@@ -122,6 +124,10 @@ int upload(bllm_prefix_groups* pg, hipStream_t stream) {
     pg->d.arrivals = reinterpret_cast<int32_t*>(place(sizes[9]));
     pg->d.sl_prefix_tile_items = reinterpret_cast<Item*>(place(sizes[10]));
     pg->d.sl_prefix_row_split = reinterpret_cast<RowSplit*>(place(sizes[11]));
+    pg->d.th_pair_items = reinterpret_cast<Item*>(place(sizes[12]));
+    pg->d.th_prefix_tile_items = reinterpret_cast<Item*>(place(sizes[13]));
+    pg->d.th_suffix_tile_items = reinterpret_cast<Item*>(place(sizes[14]));
+    pg->d.th_prefix_row_split = reinterpret_cast<RowSplit*>(place(sizes[15]));
     e = hipMemsetAsync(pg->d.arrivals, 0, sizes[9], stream);      // at create only; the kernels keep them at zero
     if (e != hipSuccess) return hip_fail(e, "hipMemsetAsync(arrival counters)");
 
@@ -143,6 +149,10 @@ int upload(bllm_prefix_groups* pg, hipStream_t stream) {
     BLLM_UP(pg->d.row_kv_dst, p.row_kv_dst);
     BLLM_UP(pg->d.sl_prefix_tile_items, p.sl_prefix_tile_items);
     BLLM_UP(pg->d.sl_prefix_row_split, p.sl_prefix_row_split);
+    BLLM_UP(pg->d.th_pair_items, p.th_pair_items);
+    BLLM_UP(pg->d.th_prefix_tile_items, p.th_prefix_tile_items);
+    BLLM_UP(pg->d.th_suffix_tile_items, p.th_suffix_tile_items);
+    BLLM_UP(pg->d.th_prefix_row_split, p.th_prefix_row_split);
 #undef BLLM_UP
     // The source vectors are pageable, so the copies above are staged; the
     // synchronisation makes the handle usable from any stream afterwards.
@@ -251,6 +261,14 @@ int bllm_prefix_group_metadata(const bllm_prefix_groups* pg, bllm_packing_view* 
     v->n_suffix_ws_rows = p.n_suffix_ws_rows;
     v->prefix_row_split = reinterpret_cast<const int32_t*>(p.prefix_row_split.data());
     v->suffix_row_split = reinterpret_cast<const int32_t*>(p.suffix_row_split.data());
+    v->n_through_pairs = static_cast<int32_t>(p.th_pair_items.size() / 2);
+    v->through_pair_items = reinterpret_cast<const int32_t*>(p.th_pair_items.data());
+    v->n_through_prefix_tile_items = static_cast<int32_t>(p.th_prefix_tile_items.size());
+    v->through_prefix_tile_items = reinterpret_cast<const int32_t*>(p.th_prefix_tile_items.data());
+    v->n_through_suffix_tile_items = static_cast<int32_t>(p.th_suffix_tile_items.size());
+    v->through_suffix_tile_items = reinterpret_cast<const int32_t*>(p.th_suffix_tile_items.data());
+    v->n_through_prefix_ws_rows = p.n_th_prefix_ws_rows;
+    v->through_prefix_row_split = p.through ? reinterpret_cast<const int32_t*>(p.th_prefix_row_split.data()) : nullptr;
     return BLLM_OK;
 }
 
@@ -268,10 +286,21 @@ int bllm_prefix_group_destroy(bllm_prefix_groups* pg) {
 // The attention kernels of one pass (matrix-core tiles, then streaming items), without the
 // combine of split KV ranges.  With a merge target they write the merged final output instead
 // of the pass's own partial (o_part / lse_part are then unused).
+// `th` (one-call path of a batch with p.through): the lists without the requests that go through both parts in
+// one workgroup; the prefix pass then also runs their item pairs, which write rows of the final output.
+struct ThroughArgs {
+    const void* k_own = nullptr;
+    const void* v_own = nullptr;
+    void* o_out = nullptr;
+    float* lse_out = nullptr;
+};
 static int launch_pass_kernels(const bllm_prefix_groups* pg, bool prefix, const void* q, const void* k, const void* v,
-                               float* o_part, float* lse_part, const MergeTarget& mt, void* hip_stream) {
+                               float* o_part, float* lse_part, const MergeTarget& mt, void* hip_stream,
+                               const ThroughArgs* th = nullptr) {
     const Packing& p = pg->pk;
-    const auto& tiles = prefix ? p.prefix_tile_items : p.suffix_tile_items;
+    const auto& tiles = prefix ? (th ? p.th_prefix_tile_items : p.prefix_tile_items) : (th ? p.th_suffix_tile_items : p.suffix_tile_items);
+    const Item* d_tiles = prefix ? (th ? pg->d.th_prefix_tile_items : pg->d.prefix_tile_items)
+                                 : (th ? pg->d.th_suffix_tile_items : pg->d.suffix_tile_items);
     const auto& rows = prefix ? p.prefix_row_items : p.suffix_row_items;
     const int64_t kv_rows = prefix ? p.prefix_kv_start.back() : p.req_kv_start.back();
     if (kv_rows > 0 && (!k || !v)) {
@@ -283,7 +312,7 @@ static int launch_pass_kernels(const bllm_prefix_groups* pg, bool prefix, const 
     if (!prefix && !tiles.empty() && !rows.empty() && pg->desc.n_q_heads / pg->desc.n_kv_heads <= 4 &&
         std::getenv("BLLM_TUNE_SUFFIX_SEPARATE") == nullptr) {
         // prefill chunks and decode rows in one launch: the two kinds of work run beside each other
-        e = launch_suffix_fused(c, pg->d.suffix_tile_items, static_cast<int32_t>(tiles.size()), pg->d.suffix_row_items,
+        e = launch_suffix_fused(c, d_tiles, static_cast<int32_t>(tiles.size()), pg->d.suffix_row_items,
                                 static_cast<int32_t>(rows.size()), p.suffix_stream_wpi, q, k, v, o_part, lse_part,
                                 pg->d.ws_o, pg->d.ws_lse, mt);
         if (e != hipSuccess) return hip_fail(e, "suffix pass launch");
@@ -292,10 +321,14 @@ static int launch_pass_kernels(const bllm_prefix_groups* pg, bool prefix, const 
         if (e != hipSuccess) return hip_fail(e, "keyless rows launch");
         return BLLM_OK;
     }
-    if (!tiles.empty()) {
-        e = launch_tile_attention(c, prefix ? pg->d.prefix_tile_items : pg->d.suffix_tile_items,
-                                  static_cast<int32_t>(tiles.size()), p.tile_waves, q, k, v, o_part, lse_part, pg->d.ws_o,
-                                  pg->d.ws_lse, mt);
+    if (prefix && th != nullptr) {
+        e = launch_tile_attention_through(c, pg->d.th_pair_items, static_cast<int32_t>(p.th_pair_items.size() / 2), d_tiles,
+                                          static_cast<int32_t>(tiles.size()), p.tile_waves, q, k, v, th->k_own, th->v_own,
+                                          o_part, lse_part, pg->d.ws_o, pg->d.ws_lse, th->o_out, th->lse_out);
+        if (e != hipSuccess) return hip_fail(e, "tile attention launch (two-range items)");
+    } else if (!tiles.empty()) {
+        e = launch_tile_attention(c, d_tiles, static_cast<int32_t>(tiles.size()), p.tile_waves, q, k, v, o_part, lse_part,
+                                  pg->d.ws_o, pg->d.ws_lse, mt);
         if (e != hipSuccess) return hip_fail(e, "tile attention launch");
     }
     if (!rows.empty()) {
@@ -433,7 +466,19 @@ int bllm_prefix_shared_attention(const bllm_prefix_groups* pg, const void* q, co
     const size_t row_heads = static_cast<size_t>(p.n_rows) * pg->desc.n_q_heads;
     float* o1 = static_cast<float*>(workspace);
     float* l1 = reinterpret_cast<float*>(static_cast<char*>(workspace) + align256(row_heads * pg->desc.head_dim * sizeof(float)));
-    rc = launch_pass_kernels(pg, true, q, k_prefix, v_prefix, o1, l1, MergeTarget{}, hip_stream);
+    // Prefill-chunk requests whose rows fill their own tiles go through both parts in one workgroup of the
+    // prefix launch and leave no partial; the suffix kernels then cover the other rows only.
+    const bool through = p.through && std::getenv("BLLM_TUNE_NO_THROUGH") == nullptr;
+    ThroughArgs th;
+    th.k_own = k_suffix;
+    th.v_own = v_suffix;
+    th.o_out = o_out;
+    th.lse_out = lse_out;
+    if (through && (!k_suffix || !v_suffix)) {
+        set_error("null KV pointer");
+        return BLLM_INVALID_ARG;
+    }
+    rc = launch_pass_kernels(pg, true, q, k_prefix, v_prefix, o1, l1, MergeTarget{}, hip_stream, through ? &th : nullptr);
     if (rc != BLLM_OK) return rc;
     // The suffix kernels fold every prefix partial of a row - one, or the pieces of a split prefix
     // straight from the split workspace, without a combine launch - with their own result.
@@ -442,12 +487,12 @@ int bllm_prefix_shared_attention(const bllm_prefix_groups* pg, const void* q, co
     mt.lse_a = l1;
     mt.o_out = o_out;
     mt.lse_out = lse_out;
-    if (p.prefix_has_split) {
-        mt.row_split = pg->d.prefix_row_split;
+    if (through ? p.th_prefix_has_split : p.prefix_has_split) {
+        mt.row_split = through ? pg->d.th_prefix_row_split : pg->d.prefix_row_split;
         mt.ws_o = pg->d.ws_o;
         mt.ws_lse = pg->d.ws_lse;
     }
-    return launch_pass_kernels(pg, false, q, k_suffix, v_suffix, nullptr, nullptr, mt, hip_stream);
+    return launch_pass_kernels(pg, false, q, k_suffix, v_suffix, nullptr, nullptr, mt, hip_stream, through ? &th : nullptr);
 }
 
 size_t bllm_prefix_shared_single_launch_workspace_bytes(const bllm_prefix_groups* pg) {

@@ -46,6 +46,12 @@ struct Packing {
     std::vector<Item> sl_prefix_tile_items;
     std::vector<RowSplit> sl_prefix_row_split;
     int32_t n_sl_prefix_ws_rows = 0;
+    // lists of the one-call path when prefill-chunk requests go through both parts in one workgroup: pairs of
+    // items (prefix range, own range) for those requests, and the tiles of both parts for all other rows
+    bool through = false, th_prefix_has_split = false;
+    std::vector<Item> th_pair_items, th_prefix_tile_items, th_suffix_tile_items;
+    std::vector<RowSplit> th_prefix_row_split;
+    int32_t n_th_prefix_ws_rows = 0;
     // wavefronts that share one streaming item (1, 2 or 4), per pass
     int32_t prefix_stream_wpi = 4, suffix_stream_wpi = 4;
     // wavefronts per MFMA tile workgroup (32 stacked query rows each): tile_rows = 32 * tile_waves / rho
@@ -63,6 +69,10 @@ struct DeviceLists {
     int32_t* arrivals = nullptr;   // [n_rows, Hkv] arrival counters of the single-launch path, zero between calls
     Item* sl_prefix_tile_items = nullptr;
     RowSplit* sl_prefix_row_split = nullptr;
+    Item* th_pair_items = nullptr;
+    Item* th_prefix_tile_items = nullptr;
+    Item* th_suffix_tile_items = nullptr;
+    RowSplit* th_prefix_row_split = nullptr;
     float* ws_o = nullptr;     // [ws_rows, Hq, D]
     float* ws_lse = nullptr;   // [ws_rows, Hq]
 };
@@ -112,12 +122,32 @@ struct MergeTarget {
     const float* ws_lse = nullptr;
 };
 
+// Second KV range of a matrix-core work item that takes its rows through both parts of prefix-shared
+// attention in one workgroup: after the item's own range (the shared prefix) the same rows go on, with the
+// running softmax state they have, over rows [kv_row0, kv_row0 + kv_len) of (k, v) - the request's own
+// keys, causal from vis0 - and the normalised result is the final output.  kv_len == 0: no second range.
+struct SecondRange {
+    const uint16_t* k = nullptr;
+    const uint16_t* v = nullptr;
+    int32_t kv_row0 = 0;
+    int32_t kv_len = 0;
+    int32_t vis0 = 0;
+    void* o_out = nullptr;         // [n_rows, Hq, D] bf16
+    float* lse_out = nullptr;      // [n_rows, Hq] or null
+};
+
 hipError_t launch_stream_attention(const LaunchCtx& c, const Item* items, int32_t n_items, int waves_per_item,
                                    const void* q, const void* k, const void* v, float* o_part, float* lse_part,
                                    float* ws_o, float* ws_lse, const MergeTarget& mt);
 hipError_t launch_tile_attention(const LaunchCtx& c, const Item* items, int32_t n_items, int waves, const void* q,
                                  const void* k, const void* v, float* o_part, float* lse_part, float* ws_o,
                                  float* ws_lse, const MergeTarget& mt);
+// The shared-prefix tiles of a batch together with its two-range items (pairs of items: the prefix range in
+// (k, v), then the request's own range in (k2, v2)), which write rows of the final output; one launch.
+hipError_t launch_tile_attention_through(const LaunchCtx& c, const Item* pairs, int32_t n_pairs, const Item* items,
+                                         int32_t n_items, int waves, const void* q, const void* k, const void* v,
+                                         const void* k2, const void* v2, float* o_part, float* lse_part, float* ws_o,
+                                         float* ws_lse, void* o_out, float* lse_out);
 // Chunk tiles and streaming items of the distinct-suffix pass as workgroups of one launch (bf16, head_dim 128,
 // both lists non-empty).
 hipError_t launch_suffix_fused(const LaunchCtx& c, const Item* tiles, int32_t n_tiles, const Item* rows, int32_t n_rows_items,

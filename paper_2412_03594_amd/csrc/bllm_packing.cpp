@@ -19,6 +19,7 @@ constexpr int kSplitWhenBelow = 512;    // split the prefix when fewer tile item
 constexpr int kSplitTargetItems = 512;  // two workgroups per compute unit
 constexpr int kSingleLaunchSplitBelow = 128;   // the single launch splits prefixes when fewer tiles than this exist ...
 constexpr int kSingleLaunchTargetItems = 128;  // ... into about half a tile per compute unit
+constexpr int64_t kThroughGain = 400;         // a chunk goes through both parts in one workgroup when pad * prefix_len < this * q_len
 constexpr int kMinSplitLen = 512;       // shorter splits cost more in partial-result traffic than they gain
 
 bool fits_i32(int64_t v) { return v >= 0 && v <= std::numeric_limits<int32_t>::max(); }
@@ -172,16 +173,37 @@ int build_packing(const bllm_layer_desc& desc, int32_t n_groups, const int32_t* 
         int32_t* ws_rows;
         bool* has_split;
     };
-    auto build_prefix_tiles = [&](int split_when_below, int target_items, const PrefixTiles& out) -> int {
+    // Runs of consecutive packed rows of group g that the shared-prefix tiles cover: the whole group, or what
+    // is left of it between the requests flagged in `skip` (indexed by packed request).
+    struct Run { int32_t row0, rows; };
+    auto group_runs = [&](int32_t g, const std::vector<char>* skip) {
+        std::vector<Run> runs;
+        Run cur{0, 0};
+        for (int32_t a = p.group_req_start[g]; a < p.group_req_start[g + 1]; ++a) {
+            const int32_t row0 = p.req_row_start[a], n = p.req_row_start[a + 1] - row0;
+            if (skip != nullptr && (*skip)[a]) {
+                if (cur.rows > 0) runs.push_back(cur);
+                cur = Run{0, 0};
+            } else {
+                if (cur.rows == 0) cur.row0 = row0;
+                cur.rows += n;
+            }
+        }
+        if (cur.rows > 0) runs.push_back(cur);
+        return runs;
+    };
+    auto build_prefix_tiles = [&](int split_when_below, int target_items, const PrefixTiles& out,
+                                  const std::vector<char>* skip = nullptr, int64_t other_items = 0) -> int {
         const int32_t br = p.tile_rows;
-        int64_t base_items = 0;
+        int64_t base_items = other_items;
         int32_t max_lp = 0;
         for (int32_t g = 0; g < n_groups; ++g) {
-            const int32_t rows = p.group_row_start[g + 1] - p.group_row_start[g];
             base_items += static_cast<int64_t>(ceil_div(p.group_prefix_row_start[g + 1] - p.group_prefix_row_start[g], br)) * n_kv_heads;
-            if (rows == 0 || prefix_len[g] == 0) continue;
-            base_items += static_cast<int64_t>(ceil_div(rows, br)) * n_kv_heads;
-            max_lp = std::max(max_lp, prefix_len[g]);
+            if (prefix_len[g] == 0) continue;
+            for (const Run& run : group_runs(g, skip)) {
+                base_items += static_cast<int64_t>(ceil_div(run.rows, br)) * n_kv_heads;
+                max_lp = std::max(max_lp, prefix_len[g]);
+            }
         }
         *out.split_len = 0;
         if (base_items > 0 && base_items < split_when_below) {
@@ -206,9 +228,9 @@ int build_packing(const bllm_layer_desc& desc, int32_t n_groups, const int32_t* 
                 for (int32_t j = 0; j < n_kv_heads; ++j)
                     out.items->push_back(Item{prow0 + i0, n, j, p.prefix_kv_start[g], first_vis + n - 1, first_vis, -1, 0});
             }
-            const int32_t row0 = p.group_row_start[g];
-            const int32_t rows = p.group_row_start[g + 1] - row0;
-            if (rows == 0) continue;
+            for (const Run& run : group_runs(g, skip)) {
+            const int32_t row0 = run.row0;
+            const int32_t rows = run.rows;
             const int32_t lp = prefix_len[g];
             const int32_t n_sp = (split_len > 0 && lp > split_len) ? ceil_div(lp, split_len) : 1;
             const int32_t ws_base = static_cast<int32_t>(ws_rows);
@@ -238,6 +260,7 @@ int build_packing(const bllm_layer_desc& desc, int32_t n_groups, const int32_t* 
                         out.items->push_back(it);
                     }
                 }
+            }
             }
         }
         *out.ws_rows = static_cast<int32_t>(ws_rows);
@@ -315,6 +338,59 @@ int build_packing(const bllm_layer_desc& desc, int32_t n_groups, const int32_t* 
     // chunks, enough streaming items to fill the chip beside the tiles, up to 4 query heads per KV head).
     // There the tiles share the compute units with the streaming items from the start, and half a tile per
     // compute unit measured best (l8b_decode: 2 pieces 74.8 us, 3 pieces 75.9, 4 pieces 77.8, unsplit 98.9).
+    // Requests with prefill chunks whose rows fill their own tiles go through both parts in one workgroup (a
+    // pair of items: the prefix range, then the request's own causal range), which leaves no partial result to
+    // write and read back; the price is the padding of the request's last row block over the prefix, which the
+    // shared-prefix tiles would have filled with the next request's rows.  Taken when that padding costs less
+    // matrix-core time than the partial costs memory time: pad * prefix_len * 4 D flops a query head at about
+    // 1 PFLOP/s against q_len * 2 (4 D + 4) bytes at about 5 TB/s, i.e. pad * prefix_len < 400 * q_len.
+    p.through = false;
+    p.th_pair_items.clear();
+    p.th_prefix_tile_items.clear();
+    p.th_suffix_tile_items.clear();
+    p.th_prefix_row_split.clear();
+    p.n_th_prefix_ws_rows = 0;
+    p.th_prefix_has_split = false;
+    if (mfma && !p.suffix_tile_items.empty()) {
+        const int32_t br = p.tile_rows;
+        std::vector<char> through(p.n_active, 0);
+        for (int32_t a = 0; a < p.n_active; ++a) {
+            const int32_t r = p.perm_req[a];
+            const int32_t nq = req_q_len[r], s = req_suffix_len[r], g = req_group[r], row0 = p.req_row_start[a];
+            if (nq < 2) continue;
+            const int64_t pad = static_cast<int64_t>(ceil_div(nq, br)) * br - nq;
+            if (pad * prefix_len[g] < kThroughGain * static_cast<int64_t>(nq)) {
+                through[a] = 1;
+                p.through = true;
+                for (int32_t i0 = 0; i0 < nq; i0 += br) {
+                    const int32_t n = std::min(br, nq - i0);
+                    for (int32_t j = 0; j < n_kv_heads; ++j) {
+                        p.th_pair_items.push_back(Item{row0 + i0, n, j, p.prefix_kv_start[g], prefix_len[g], prefix_len[g], -1, 0});
+                        p.th_pair_items.push_back(Item{row0 + i0, n, j, p.req_kv_start[r], s - nq + i0 + n, s - nq + i0 + 1, -1, 0});
+                    }
+                }
+            } else {
+                for (int32_t i0 = 0; i0 < nq; i0 += br) {
+                    const int32_t n = std::min(br, nq - i0);
+                    for (int32_t j = 0; j < n_kv_heads; ++j)
+                        p.th_suffix_tile_items.push_back(
+                            Item{row0 + i0, n, j, p.req_kv_start[r], s - nq + i0 + n, s - nq + i0 + 1, -1, 0});
+                }
+            }
+        }
+        if (p.through) {
+            // the pairs keep their order (group, request, row block, KV head): sorting them by length measured
+            // slower (l8b_mixed 0.739 ms as generated, 0.747 by prefix length, 0.757 by total length)
+            int32_t split_len = 0;
+            const int rc = build_prefix_tiles(kSplitWhenBelow, kSplitTargetItems,
+                                              PrefixTiles{&p.th_prefix_tile_items, &p.th_prefix_row_split, &split_len,
+                                                          &p.n_th_prefix_ws_rows, &p.th_prefix_has_split},
+                                              &through, static_cast<int64_t>(p.th_pair_items.size() / 2));
+            if (rc != BLLM_OK) return rc;
+        } else {
+            p.th_suffix_tile_items.clear();
+        }
+    }
     p.single_launch = false;
     if (mfma && rho <= 4 && p.suffix_tile_items.empty() && p.suffix_row_items.size() >= 1024) {
         int32_t split_len = 0;

@@ -90,7 +90,8 @@ template <int NW, int BN, bool kCoherent = false>
 __device__ __forceinline__ void tile_attention_body(
     const Item it, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const uint16_t* __restrict__ v, float* __restrict__ o_part, float* __restrict__ lse_part, float* __restrict__ ws_o,
-    float* __restrict__ ws_lse, int n_q_heads, int n_kv_heads, int log2_rho, float scale, const MergeTarget& mt) {
+    float* __restrict__ ws_lse, int n_q_heads, int n_kv_heads, int log2_rho, float scale, const MergeTarget& mt,
+    const SecondRange& r2 = SecondRange{}) {
     constexpr int kBN = BN;
     constexpr int kKvb = BN / 32;                    // 32-row blocks of S^T per step
     constexpr int kTileBytes = kBN * kRowBytes;
@@ -108,7 +109,8 @@ __device__ __forceinline__ void tile_attention_body(
     const int h = lane >> 5;         // lane half
     const int rho = 1 << log2_rho;
     const int head0 = it.kv_head << log2_rho;
-    const int kv_len = it.kv_len;
+    int kv_len = it.kv_len;          // of the range being worked on
+    const bool through = r2.kv_len > 0;
     const float c2 = scale * kLog2e;
 
     float* dst_o;
@@ -126,7 +128,7 @@ __device__ __forceinline__ void tile_attention_body(
     const int tok = m_row >> log2_rho;
     const int hd = m_row & (rho - 1);
     const bool row_ok = tok < it.n_rows;
-    const int vis = (row_ok && it.vis0 + tok < kv_len) ? it.vis0 + tok : kv_len;   // padding rows see everything
+    int vis = (row_ok && it.vis0 + tok < kv_len) ? it.vis0 + tok : kv_len;   // padding rows see everything
 
     // (row, head) index of this lane's query in the [n_rows, Hq] arrays of a fused merge
     const size_t rh = static_cast<size_t>(it.q_row0 + tok) * n_q_heads + head0 + hd;
@@ -153,7 +155,7 @@ __device__ __forceinline__ void tile_attention_body(
         store_out4<true>(mt.o_out, rh * kD + x, r.x, r.y, r.z, r.w);
         return lse;
     };
-    if (kv_len <= 0 && mt.o_a != nullptr) {      // empty part, fused merge: the other part passes through
+    if (kv_len <= 0 && !through && mt.o_a != nullptr) {      // empty part, fused merge: the other part passes through
         if (row_ok) {
             float lse = -INFINITY;
             for (int x = h * 64; x < h * 64 + 64; x += 4) lse = fold_and_store(x, -INFINITY, make_float4(0.f, 0.f, 0.f, 0.f));
@@ -161,7 +163,7 @@ __device__ __forceinline__ void tile_attention_body(
         }
         return;
     }
-    if (kv_len <= 0) {               // empty part: output 0, log-sum-exp -inf
+    if (kv_len <= 0 && !through) {   // empty part: output 0, log-sum-exp -inf
         if (row_ok) {
             float* orow = dst_o + (static_cast<size_t>(tok) * n_q_heads + hd) * kD;
             for (int x = h * 64; x < h * 64 + 64; x += 4) store_partial4<kCoherent>(orow + x, 0.f, 0.f, 0.f, 0.f);
@@ -172,7 +174,7 @@ __device__ __forceinline__ void tile_attention_body(
 
     // smallest visible count among this wavefront's rows: tiles that end below it need no mask
     const int wave_tok_lo = (32 * wave) >> log2_rho;
-    const int wave_min_vis = wave_tok_lo < it.n_rows ? min(kv_len, it.vis0 + wave_tok_lo) : kv_len;
+    int wave_min_vis = wave_tok_lo < it.n_rows ? min(kv_len, it.vis0 + wave_tok_lo) : kv_len;
 
     // ---- Q fragments (B operand of S^T = K Q^T): Q[query = col][d = 16 t + 8 h + 0..7] -------
     bf16x8 qreg[8];
@@ -204,7 +206,7 @@ __device__ __forceinline__ void tile_attention_body(
                               (static_cast<size_t>(it.kv_row0) * n_kv_heads + it.kv_head) * kRowBytes;
     const unsigned char* vg = reinterpret_cast<const unsigned char*>(v) +
                               (static_cast<size_t>(it.kv_row0) * n_kv_heads + it.kv_head) * kRowBytes;
-    const int n_tiles = (kv_len + kBN - 1) / kBN;
+    int n_tiles = (kv_len + kBN - 1) / kBN;
     uint32_t goff_k[kInstrPerWave], goff_v[kInstrPerWave];
 #pragma unroll
     for (int jj = 0; jj < kInstrPerWave; ++jj) {
@@ -262,7 +264,7 @@ __device__ __forceinline__ void tile_attention_body(
             va[db] = kTileBytes + (4 * h + e) * kRowBytes + (v_unit(4 * db + 2 * g1 + (c >> 1), e) << 4) + (c & 1) * 8;
     }
 
-    dma_tile(0, smem_even);
+    if (n_tiles > 0) dma_tile(0, smem_even);
     // The first other partial's log-sum-exp is requested now, behind the first tile, so the epilogue finds
     // it there.
     float first_other_l = -INFINITY;
@@ -384,10 +386,39 @@ __device__ __forceinline__ void tile_attention_body(
         step(tile, smem_even, smem_odd);
         if (tile + 1 < n_tiles) step(tile + 1, smem_odd, smem_even);
     }
+    if (through) {
+        // The same rows go on over their second range with the running state they have: the online softmax
+        // is the reduction of the two parts.  Both buffers are free (the last step ended with a barrier).
+        kv_len = r2.kv_len;
+        vis = (row_ok && r2.vis0 + tok < kv_len) ? r2.vis0 + tok : kv_len;
+        wave_min_vis = wave_tok_lo < it.n_rows ? min(kv_len, r2.vis0 + wave_tok_lo) : kv_len;
+        kg = reinterpret_cast<const unsigned char*>(r2.k) + (static_cast<size_t>(r2.kv_row0) * n_kv_heads + it.kv_head) * kRowBytes;
+        vg = reinterpret_cast<const unsigned char*>(r2.v) + (static_cast<size_t>(r2.kv_row0) * n_kv_heads + it.kv_head) * kRowBytes;
+        n_tiles = (kv_len + kBN - 1) / kBN;
+        dma_tile(0, smem_even);
+        wait_vector_memory<0>();
+        __syncthreads();
+        for (int tile = 0; tile < n_tiles; tile += 2) {
+            step(tile, smem_even, smem_odd);
+            if (tile + 1 < n_tiles) step(tile + 1, smem_odd, smem_even);
+        }
+    }
 
     // ---- epilogue: normalise and store O (transposed back), log-sum-exp --------------------------
     const float ltot = l_run + __shfl_xor(l_run, 32);
-    if (row_ok && mt.o_a != nullptr) {
+    if (through) {
+        // both parts are in the accumulators: the normalised result is the final output
+        if (row_ok) {
+            const float inv = 1.f / ltot;                        // every row sees its own key
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    store_out4<true>(r2.o_out, rh * kD + 32 * db + 8 * i + 4 * h, oacc[db][4 * i] * inv, oacc[db][4 * i + 1] * inv,
+                                     oacc[db][4 * i + 2] * inv, oacc[db][4 * i + 3] * inv);
+            if (h == 0 && r2.lse_out != nullptr) r2.lse_out[rh] = (m_run + log2f(ltot)) * kLn2;
+        }
+    } else if (row_ok && mt.o_a != nullptr) {
         // Fused merge: this part is (O / l, log-sum-exp lb), the other part comes from memory.  The
         // weights of all parts (relative to their common maximum) come first, then every partial
         // is added with its 16 row pieces fetched at once.

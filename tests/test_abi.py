@@ -98,7 +98,9 @@ def test_host_only_handle_refuses_device_calls():
 
 
 WORK_KEYS = ["prefix_tile_items", "prefix_row_items", "suffix_tile_items", "suffix_row_items", "prefix_row_split",
-             "suffix_row_split", "prefix_split_len", "suffix_split_len", "n_prefix_ws_rows", "n_suffix_ws_rows"]
+             "suffix_row_split", "prefix_split_len", "suffix_split_len", "n_prefix_ws_rows", "n_suffix_ws_rows",
+             "through_pair_items", "through_prefix_tile_items", "through_suffix_tile_items", "through_prefix_row_split",
+             "n_through_prefix_ws_rows"]
 
 
 def check_work_lists(b):
@@ -109,7 +111,7 @@ def check_work_lists(b):
     ref = build_work_lists(ref_meta, b.prefix_len, b.req_suffix_len, b.req_q_len, L.n_q_heads, L.n_kv_heads,
                            L.head_dim, L.dtype == workload.BF16, m["tile_rows"])
     for k in WORK_KEYS:
-        assert np.array_equal(np.asarray(m[k]), np.asarray(ref[k])), k
+        assert np.asarray(m[k]).shape == np.asarray(ref[k]).shape and np.array_equal(np.asarray(m[k]), np.asarray(ref[k])), k
     return m
 
 
@@ -238,3 +240,88 @@ def test_one_call_workspace_tells_which_form_runs():
     pg = host_pack(b)
     assert 2 * bllm.prefix_shared_workspace_bytes(pg) == bllm.prefix_shared_single_launch_workspace_bytes(pg)
     pg.destroy()
+
+
+def test_through_lists_hand_case():
+    """Which prefill chunks go through both parts in one workgroup, on a batch small enough to write the
+    lists out by hand.  Hq 8, Hkv 2: 32 token rows per tile.  Group 0 (prefix 1000): a 64-row chunk (no
+    padding: through), a 40-row chunk (24 padded rows x 1000 >= 400 x 40: stays two-pass), a decode row;
+    group 1 (prefix 10): a 33-row chunk (31 x 10 < 400 x 33: through)."""
+    L = workload.Layer(8, 2, 128, workload.BF16)
+    b = workload.Batch("hand", L, np.array([1000, 10], np.int32), np.array([0, 0, 0, 1], np.int32),
+                       np.array([100, 50, 7, 33], np.int32), np.array([64, 40, 1, 33], np.int32))
+    m = check_work_lists(b)
+    assert m["tile_rows"] == 32
+    # packed order: group 0: the decode row (row 0), the 64-row chunk (rows 1..64), the 40-row chunk (65..104);
+    # group 1: the 33-row chunk (105..137).  Suffix KV rows: 0.., 100.., 150.., 157..
+    assert list(m["perm_req"]) == [2, 0, 1, 3]
+    pairs = [[list(a), list(c)] for a, c in m["through_pair_items"]]
+    want = []
+    for i0, n, vis0 in ((1, 32, 37), (33, 32, 69)):                       # positions 36..67 and 68..99 of request 0
+        for j in (0, 1):
+            want.append([[i0, n, j, 0, 1000, 1000, -1, 0], [i0, n, j, 0, vis0 + n - 1, vis0, -1, 0]])
+    for i0, n, vis0 in ((105, 32, 1), (137, 1, 33)):                      # request 3 starts at position 0
+        for j in (0, 1):
+            want.append([[i0, n, j, 1000, 10, 10, -1, 0], [i0, n, j, 157, vis0 + n - 1, vis0, -1, 0]])
+    assert pairs == want
+    # what is left for the two passes: the decode row and the 40-row chunk.  They are two runs of rows (the
+    # through request lies between them); with 8 pairs there are 8 + 2 + 4 = 14 < 512 tiles, so the prefix is
+    # split into 512-row pieces.
+    pt = [list(x) for x in m["through_prefix_tile_items"]]
+    assert sorted(pt) == sorted(
+        [[0, 1, j, 0, 512, 512, 0, 0] for j in (0, 1)] + [[0, 1, j, 512, 488, 488, 1, 0] for j in (0, 1)] +
+        [[65 + i0, n, j, off, ln, ln, 2 + c * 40 + i0, 0] for c, (off, ln) in enumerate(((0, 512), (512, 488)))
+         for i0, n in ((0, 32), (32, 8)) for j in (0, 1)])
+    assert m["n_through_prefix_ws_rows"] == 2 + 80
+    assert [list(x) for x in m["through_prefix_row_split"][[0, 1, 65, 104, 105]]] == \
+        [[0, 1, 2], [0, 0, 0], [2, 40, 2], [41, 40, 2], [0, 0, 0]]
+    assert [list(x) for x in m["through_suffix_tile_items"]] == \
+        [[65 + i0, n, j, 100, 10 + i0 + n, 10 + i0 + 1, -1, 0] for i0, n in ((0, 32), (32, 8)) for j in (0, 1)]
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_through_lists_cover_every_row_head_once(seed):
+    """With the through lists, every (request row, KV head) still gets its whole prefix and its own keys
+    exactly once: either as one pair, or from the tiles of the two passes."""
+    b = workload.ragged_toy(seed, dtype=workload.BF16, n_q_heads=8, n_kv_heads=2, head_dim=128, n_groups=4,
+                            max_prefix=700, max_group=6, max_suffix=300, max_chunk=150)
+    if seed % 2:
+        b = workload.with_prefix_prefill(b, seed=seed)
+    m = host_pack(b).metadata()
+    T, H = m["n_rows"], b.layer.n_kv_heads
+    first_prefix_row = m["group_prefix_row_start"][0]
+    row_group = np.concatenate([b.req_group[m["row_req"][:first_prefix_row]],
+                                np.repeat(np.arange(b.n_groups), np.diff(m["group_prefix_row_start"]))])
+    want_prefix = np.where(np.arange(T) < first_prefix_row, b.prefix_len[row_group], m["row_pos"] + 1)
+    if len(m["through_pair_items"]) == 0:
+        assert len(m["through_prefix_tile_items"]) == 0 and len(m["through_suffix_tile_items"]) == 0
+        pytest.skip("no request of this batch qualifies")
+    got_prefix = np.zeros((T, H), dtype=np.int64)
+    own = np.zeros((T, H), dtype=np.int64)
+    in_pair = np.zeros(T, dtype=bool)
+    for first, second in m["through_pair_items"]:
+        assert list(first[:3]) == list(second[:3]) and first[6] == -1 and second[6] == -1
+        g = row_group[first[0]]
+        assert first[3] == m["prefix_kv_start"][g] and first[4] == first[5] == b.prefix_len[g]
+        for i in range(first[1]):
+            t = first[0] + i
+            in_pair[t] = True
+            got_prefix[t, first[2]] += first[4]
+            assert second[3] == m["req_kv_start"][m["row_req"][t]]
+            assert min(second[4], second[5] + i) == m["row_pos"][t] + 1
+            own[t, first[2]] += 1
+    for it in m["through_prefix_tile_items"]:
+        for i in range(it[1]):
+            assert not in_pair[it[0] + i]
+            got_prefix[it[0] + i, it[2]] += min(it[4], it[5] + i)
+    for it in list(m["through_suffix_tile_items"]) + list(m["suffix_row_items"]):
+        for i in range(it[1]):
+            t = it[0] + i
+            assert not in_pair[t] and min(it[4], it[5] + i) == m["row_pos"][t] + 1
+            own[t, it[2]] += 1
+    assert np.array_equal(got_prefix, np.repeat(want_prefix[:, None], H, axis=1))
+    assert np.all(own[:first_prefix_row] == 1) and np.all(own[first_prefix_row:] == 0)
+    # a request is either wholly in pairs or not at all
+    for a in range(m["n_active"]):
+        rows = in_pair[m["req_row_start"][a]:m["req_row_start"][a + 1]]
+        assert rows.all() or not rows.any()

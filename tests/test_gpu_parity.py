@@ -503,3 +503,27 @@ def test_random_batches_all_forms(seed):
     if seed % 3 == 0:
         b = workload.with_prefix_prefill(b, seed=seed, max_rows=int(rng.choice([50, 400])) if seed % 2 else None)
     check_all(b, workload.draw_values(b), append=(seed % 2 == 0))
+
+
+@pytest.mark.parametrize("hq,hkv", [(8, 2), (32, 8), (8, 1), (4, 4)])
+def test_chunks_taken_through_both_parts_in_one_workgroup(hq, hkv):
+    """The one-call path of a batch with prefill chunks: chunks that fill their own tiles run as pairs of items
+    (prefix range, then own causal range, one running softmax), the others and the decode rows as two passes.
+    A group with an empty prefix, a chunk that ends in a ragged row block, chunks of a few rows over a long
+    prefix (which stay two-pass), decode rows between them and prefix-prefill rows, all against the oracle."""
+    import paper_2412_03594_amd as bllm
+    L = workload.Layer(hq, hkv, 128, workload.BF16)
+    br = 128 // (hq // hkv)
+    prefix_len = np.array([1000, 0, 70, 333], np.int32)
+    req_group = np.array([0, 0, 0, 0, 1, 1, 2, 2, 3, 3, 0], np.int32)
+    req_q_len = np.array([2 * br, br + 3, 1, 3, 3 * br, 1, br + 1, 1, 4 * br + 5, 2, 1], np.int32)
+    req_suffix_len = req_q_len + np.array([36, 0, 99, 17, 0, 5, 200, 64, 129, 0, 700], np.int32)
+    b = workload.Batch("through", L, prefix_len, req_group, req_suffix_len.astype(np.int32), req_q_len,
+                       prefix_q_len=np.array([0, 0, 70, 40], np.int32))
+    pg = bllm.prefix_group_create(layer_tuple(L), b.prefix_len, b.req_group, b.req_suffix_len, b.req_q_len, host_only=True,
+                                  prefix_q_len=b.prefix_q_len)
+    m = pg.metadata()
+    assert len(m["through_pair_items"]) > 0 and len(m["through_suffix_tile_items"]) > 0
+    assert len(m["through_prefix_tile_items"]) > 0
+    pg.destroy()
+    check_all(b, workload.draw_values(b))
