@@ -30,8 +30,8 @@ MEASURED_TRAFFIC_BYTES = {
                    "single_launch": 398.4e6},
     "rank_longprefix": {"suffix": 332.2e6, "prefix": 231.8e6, "merge": 43.0e6, "suffix_merged": 341.0e6,
                         "one_call": 540.6e6, "single_launch": 540.6e6},
-    "l8b_mixed": {"suffix": 852.3e6, "prefix": 692.0e6, "merge": 709.4e6, "suffix_merged": 1004.1e6, "one_call": 1696.1e6,
-                  "single_launch": 2133.2e6},
+    "l8b_mixed": {"suffix": 852.3e6, "prefix": 692.0e6, "merge": 709.4e6, "suffix_merged": 1004.1e6, "one_call": 987.4e6,
+                  "single_launch": 998.5e6},
 }
 
 
@@ -383,15 +383,19 @@ def roofline_of(res):
         res["schedule"], ("prefix", "suffix_merged"))
     if res["schedule"] == "one_call" and res["one_call_single"]:
         in_step = ("single_launch",)
+    elif res["schedule"] == "one_call" and len(res["meta"].get("through_pair_items", ())) > 0:
+        in_step = ("one_call",)          # the prefix launch also runs the prefill chunks' own ranges: not a pass of its own
     name = max(in_step, key=lambda k: t[k])
     traffic = MEASURED_TRAFFIC_BYTES.get(res["batch"].name, {}).get(name)
     w = res["work"][name]
     sec = t[name] * 1e-3
     # arithmetic intensity decides which roof bounds the pass
     ai = w["flops"] / max(w["bytes"], 1.0)
-    if name in ("prefix", "single_launch") and ai > PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9):
+    if name in ("prefix", "single_launch", "one_call") and ai > PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9):
         a = w["flops"] / sec / 1e12
         return {"kernel": "tile_attention_kernel (shared-prefix pass)" if name == "prefix" else
+                "tile_through_kernel (shared-prefix tiles + prefill chunks taken through both parts), then the suffix "
+                "kernels of the other rows" if name == "one_call" else
                 "hfused_attention_kernel (prefix tiles, chunk tiles and streaming items in one launch)",
                 "bound": "mfma", "achieved": round(a, 2),
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(a / PEAK_BF16_TFLOPS, 4), "traffic": traffic}
@@ -399,6 +403,8 @@ def roofline_of(res):
     kern = {"prefix": "tile_attention_kernel (shared-prefix pass)",
             "suffix": "stream_attention_kernel (distinct-suffix pass)", "merge": "lse_merge_kernel",
             "suffix_merged": "stream_attention_kernel (distinct-suffix pass, reduction in the epilogue)",
+            "one_call": "tile_through_kernel (shared-prefix tiles + prefill chunks taken through both parts), then the "
+                        "suffix kernels of the other rows",
             "single_launch": "hfused_attention_kernel (prefix tiles, chunk tiles and streaming items in one launch)"}[name]
     return {"kernel": kern, "bound": "hbm", "achieved": round(a, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
             "frac": round(a / PEAK_HBM_GBS, 4), "traffic": traffic}

@@ -539,6 +539,16 @@ int bllm_prefix_shared_attention_single_launch(const bllm_prefix_groups* pg, con
     lists.n_suffix_rows = static_cast<int32_t>(p.suffix_row_items.size());
     lists.n_request_rows = p.group_prefix_row_start[0];
     lists.prefix_row_split = p.single_launch ? pg->d.sl_prefix_row_split : pg->d.prefix_row_split;
+    if (p.through && std::getenv("BLLM_TUNE_NO_THROUGH") == nullptr) {
+        // prefill chunks that fill their own tiles: both parts in one workgroup, no partial, no arrival
+        lists.pairs = pg->d.th_pair_items;
+        lists.n_pairs = static_cast<int32_t>(p.th_pair_items.size() / 2);
+        lists.prefix_tiles = pg->d.th_prefix_tile_items;
+        lists.n_prefix_tiles = static_cast<int32_t>(p.th_prefix_tile_items.size());
+        lists.suffix_tiles = pg->d.th_suffix_tile_items;
+        lists.n_suffix_tiles = static_cast<int32_t>(p.th_suffix_tile_items.size());
+        lists.prefix_row_split = pg->d.th_prefix_row_split;
+    }
     lists.ws_o = pg->d.ws_o;
     lists.ws_lse = pg->d.ws_lse;
     lists.arrivals = pg->d.arrivals;

@@ -161,6 +161,8 @@ struct HFusedLists {
     const Item* prefix_tiles;
     const Item* suffix_tiles;
     const Item* suffix_rows;
+    const Item* pairs = nullptr;          // two-range items (2 items each), or null
+    int32_t n_pairs = 0;
     int32_t n_prefix_tiles, n_suffix_tiles, n_suffix_rows, n_request_rows;
     const RowSplit* prefix_row_split;
     float* ws_o;

@@ -3,8 +3,10 @@
 // its own tiling, which removes the tail of one kernel before the next and the launch gaps).
 //
 // Workgroup b of the grid takes, in this order, a matrix-core tile of the shared-prefix part, a
-// matrix-core tile of a prefill chunk of the distinct part, or 4 / WPI streaming items (decode
-// rows).  Every part writes its fp32 partial result to the workspace exactly as the separate
+// two-range item (a prefill chunk that fills its own tiles: prefix range, then the request's own
+// range, final output straight from the accumulators - it exchanges nothing and arrives nowhere), a
+// matrix-core tile of another prefill chunk of the distinct part, or 4 / WPI streaming items (decode
+// rows).  Every other part writes its fp32 partial result to the workspace exactly as the separate
 // passes do; then it ARRIVES at the counter of each (token row, KV head) it covered.  The part
 // that arrives last at a counter reduces all partials of that row and head through online
 // softmax and writes the final output (Sec. 5).  Nobody waits for anybody: there is no spinning,
@@ -34,7 +36,8 @@ struct HFusedArgs {
     const Item* prefix_tiles;
     const Item* suffix_tiles;
     const Item* suffix_rows;
-    int n_prefix_tiles, n_suffix_tiles, n_suffix_rows;
+    const Item* pairs;    // two-range items: the prefix range, then the request's own range (2 items each)
+    int n_prefix_tiles, n_suffix_tiles, n_suffix_rows, n_pairs;
     const uint16_t* q;
     const uint16_t* k_prefix;
     const uint16_t* v_prefix;
@@ -69,17 +72,40 @@ __global__ __launch_bounds__(kThreads, RHO == 8 ? 1 : 2) void hfused_attention_k
     int n_units;                 // (token row, KV head) pairs this workgroup produced a partial for
     int unit_row = 0, unit_head = 0;     // the pair of thread tid, for tid < n_units
     const MergeTarget none{};
-    if (b < a.n_prefix_tiles + a.n_suffix_tiles) {
-        const bool prefix = b < a.n_prefix_tiles;
-        const Item it = prefix ? a.prefix_tiles[b] : a.suffix_tiles[b - a.n_prefix_tiles];
-        tile_detail::tile_attention_body<4, 64, true>(it, a.q, prefix ? a.k_prefix : a.k_suffix, prefix ? a.v_prefix : a.v_suffix,
-                                                prefix ? a.o1 : a.o2, prefix ? a.l1 : a.l2, a.ws_o, a.ws_lse, a.n_q_heads,
-                                                a.n_kv_heads, a.log2_rho, a.scale, none);
-        n_units = it.n_rows;
+    // role of this workgroup: a matrix-core item (prefix tiles, pairs, chunk tiles in this order), else block
+    // sb of streaming items (they come last and fill the slots the long items leave; placing them right after
+    // the prefix tiles measured slower: l8b_mixed 0.784 against 0.746 ms)
+    const int n_tile_slots = a.n_prefix_tiles + a.n_pairs + a.n_suffix_tiles;
+    const int tile_slot = b;
+    const int sb = b - n_tile_slots;
+    if (tile_slot < n_tile_slots) {
+        const bool prefix = tile_slot < a.n_prefix_tiles;
+        const bool pair = !prefix && tile_slot < a.n_prefix_tiles + a.n_pairs;
+        Item it;
+        SecondRange r2;
+        if (pair) {
+            // both parts of these rows in this workgroup: nothing to exchange, nobody to arrive at
+            it = a.pairs[2 * (tile_slot - a.n_prefix_tiles)];
+            const Item own = a.pairs[2 * (tile_slot - a.n_prefix_tiles) + 1];
+            r2.k = a.k_suffix;
+            r2.v = a.v_suffix;
+            r2.kv_row0 = own.kv_row0;
+            r2.kv_len = own.kv_len;
+            r2.vis0 = own.vis0;
+            r2.o_out = a.o_out;
+            r2.lse_out = a.lse_out;
+        } else {
+            it = prefix ? a.prefix_tiles[tile_slot] : a.suffix_tiles[tile_slot - a.n_prefix_tiles - a.n_pairs];
+        }
+        const bool from_prefix = prefix || pair;
+        tile_detail::tile_attention_body<4, 64, true>(it, a.q, from_prefix ? a.k_prefix : a.k_suffix,
+                                                from_prefix ? a.v_prefix : a.v_suffix, prefix ? a.o1 : a.o2,
+                                                prefix ? a.l1 : a.l2, a.ws_o, a.ws_lse, a.n_q_heads, a.n_kv_heads,
+                                                a.log2_rho, a.scale, none, r2);
+        n_units = pair ? 0 : it.n_rows;
         unit_row = it.q_row0 + tid;
         unit_head = it.kv_head;
     } else {
-        const int sb = b - a.n_prefix_tiles - a.n_suffix_tiles;
         const int first = sb * kItemsPerBlock;
         // Has every prefix part of the item's row arrived already?  One decision per item, taken by the
         // first wavefront of the WPI that share it.
@@ -200,7 +226,7 @@ __global__ __launch_bounds__(kThreads, RHO == 8 ? 1 : 2) void hfused_attention_k
 
 template <int RHO>
 hipError_t launch_for_rho(const HFusedArgs& a, int wpi, hipStream_t stream) {
-    const int tiles = a.n_prefix_tiles + a.n_suffix_tiles;
+    const int tiles = a.n_prefix_tiles + a.n_pairs + a.n_suffix_tiles;
 #define BLLM_LAUNCH_HFUSED(W)                                                                                   \
     hipLaunchKernelGGL((hfused_attention_kernel<RHO, W>), dim3(tiles + (a.n_suffix_rows * W + 3) / 4), dim3(kThreads), \
                        0, stream, a)
@@ -228,6 +254,8 @@ hipError_t launch_hfused_attention(const LaunchCtx& c, const HFusedLists& lists,
     a.n_prefix_tiles = lists.n_prefix_tiles;
     a.n_suffix_tiles = lists.n_suffix_tiles;
     a.n_suffix_rows = lists.n_suffix_rows;
+    a.pairs = lists.pairs;
+    a.n_pairs = lists.n_pairs;
     a.q = static_cast<const uint16_t*>(q);
     a.k_prefix = static_cast<const uint16_t*>(k_prefix);
     a.v_prefix = static_cast<const uint16_t*>(v_prefix);
