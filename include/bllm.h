@@ -273,7 +273,8 @@ int bllm_kv_append(const bllm_prefix_groups* pg, const void* k_new, const void* 
  * per (row block, KV head) inside the shared-prefix launch: the running softmax
  * goes on from the prefix range into the request's own keys, which is the same
  * reduction carried in registers, and no partial result of those rows is
- * written or read.  For batches
+ * written or read; the rows of prefixes being prefilled, which have no second
+ * part, are written as final output by their shared-prefix tiles likewise.  For batches
  * where it measured faster (bf16, head_dim 128, up to 4 query heads per KV head, a
  * prefix that was split along KV to fill the chip into at most 256 tiles, at least
  * 1024 streaming items, decode rows only) the call

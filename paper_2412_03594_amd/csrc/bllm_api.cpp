@@ -286,21 +286,29 @@ int bllm_prefix_group_destroy(bllm_prefix_groups* pg) {
 // The attention kernels of one pass (matrix-core tiles, then streaming items), without the
 // combine of split KV ranges.  With a merge target they write the merged final output instead
 // of the pass's own partial (o_part / lse_part are then unused).
-// `th` (one-call path of a batch with p.through): the lists without the requests that go through both parts in
-// one workgroup; the prefix pass then also runs their item pairs, which write rows of the final output.
+// `th` (one-call path on the matrix-core shapes): the shared-prefix launch writes rows of the final output itself.
+// pairs: the batch has requests that go through both parts in one workgroup (p.through); the lists without those
+// requests are used and the prefix launch also runs their item pairs.  final_prefix_rows: the rows of prefixes
+// being prefilled, which have no other part, are written as final output by their tiles, and the suffix pass
+// leaves them alone.
 struct ThroughArgs {
     const void* k_own = nullptr;
     const void* v_own = nullptr;
     void* o_out = nullptr;
     float* lse_out = nullptr;
+    bool pairs = false;
+    bool final_prefix_rows = false;
 };
 static int launch_pass_kernels(const bllm_prefix_groups* pg, bool prefix, const void* q, const void* k, const void* v,
                                float* o_part, float* lse_part, const MergeTarget& mt, void* hip_stream,
                                const ThroughArgs* th = nullptr) {
     const Packing& p = pg->pk;
-    const auto& tiles = prefix ? (th ? p.th_prefix_tile_items : p.prefix_tile_items) : (th ? p.th_suffix_tile_items : p.suffix_tile_items);
-    const Item* d_tiles = prefix ? (th ? pg->d.th_prefix_tile_items : pg->d.prefix_tile_items)
-                                 : (th ? pg->d.th_suffix_tile_items : pg->d.suffix_tile_items);
+    const bool th_lists = th != nullptr && th->pairs;
+    const bool skip_keyless = th != nullptr && th->final_prefix_rows;
+    const auto& tiles = prefix ? (th_lists ? p.th_prefix_tile_items : p.prefix_tile_items)
+                               : (th_lists ? p.th_suffix_tile_items : p.suffix_tile_items);
+    const Item* d_tiles = prefix ? (th_lists ? pg->d.th_prefix_tile_items : pg->d.prefix_tile_items)
+                                 : (th_lists ? pg->d.th_suffix_tile_items : pg->d.suffix_tile_items);
     const auto& rows = prefix ? p.prefix_row_items : p.suffix_row_items;
     const int64_t kv_rows = prefix ? p.prefix_kv_start.back() : p.req_kv_start.back();
     if (kv_rows > 0 && (!k || !v)) {
@@ -317,15 +325,18 @@ static int launch_pass_kernels(const bllm_prefix_groups* pg, bool prefix, const 
                                 pg->d.ws_o, pg->d.ws_lse, mt);
         if (e != hipSuccess) return hip_fail(e, "suffix pass launch");
         const int32_t row0 = p.group_prefix_row_start[0];
-        e = launch_keyless_rows(c, row0, p.n_rows - row0, o_part, lse_part, mt);
-        if (e != hipSuccess) return hip_fail(e, "keyless rows launch");
+        if (!skip_keyless) {
+            e = launch_keyless_rows(c, row0, p.n_rows - row0, o_part, lse_part, mt);
+            if (e != hipSuccess) return hip_fail(e, "keyless rows launch");
+        }
         return BLLM_OK;
     }
     if (prefix && th != nullptr) {
-        e = launch_tile_attention_through(c, pg->d.th_pair_items, static_cast<int32_t>(p.th_pair_items.size() / 2), d_tiles,
-                                          static_cast<int32_t>(tiles.size()), p.tile_waves, q, k, v, th->k_own, th->v_own,
-                                          o_part, lse_part, pg->d.ws_o, pg->d.ws_lse, th->o_out, th->lse_out);
-        if (e != hipSuccess) return hip_fail(e, "tile attention launch (two-range items)");
+        e = launch_tile_attention_through(c, pg->d.th_pair_items, th_lists ? static_cast<int32_t>(p.th_pair_items.size() / 2) : 0,
+                                          d_tiles, static_cast<int32_t>(tiles.size()), p.tile_waves, q, k, v, th->k_own,
+                                          th->v_own, o_part, lse_part, pg->d.ws_o, pg->d.ws_lse, th->o_out, th->lse_out,
+                                          th->final_prefix_rows ? p.group_prefix_row_start[0] : INT32_MAX);
+        if (e != hipSuccess) return hip_fail(e, "tile attention launch (rows of the final output)");
     } else if (!tiles.empty()) {
         e = launch_tile_attention(c, d_tiles, static_cast<int32_t>(tiles.size()), p.tile_waves, q, k, v, o_part, lse_part,
                                   pg->d.ws_o, pg->d.ws_lse, mt);
@@ -337,7 +348,7 @@ static int launch_pass_kernels(const bllm_prefix_groups* pg, bool prefix, const 
                                     o_part, lse_part, pg->d.ws_o, pg->d.ws_lse, mt);
         if (e != hipSuccess) return hip_fail(e, "streaming attention launch");
     }
-    if (!prefix) {
+    if (!prefix && !skip_keyless) {
         // prefix rows (they follow all request rows) have no suffix part
         const int32_t row0 = p.group_prefix_row_start[0];
         e = launch_keyless_rows(c, row0, p.n_rows - row0, o_part, lse_part, mt);
@@ -468,17 +479,23 @@ int bllm_prefix_shared_attention(const bllm_prefix_groups* pg, const void* q, co
     float* l1 = reinterpret_cast<float*>(static_cast<char*>(workspace) + align256(row_heads * pg->desc.head_dim * sizeof(float)));
     // Prefill-chunk requests whose rows fill their own tiles go through both parts in one workgroup of the
     // prefix launch and leave no partial; the suffix kernels then cover the other rows only.
-    const bool through = p.through && std::getenv("BLLM_TUNE_NO_THROUGH") == nullptr;
+    // The rows of prefixes being prefilled have no other part: on the matrix-core shapes their tiles write the
+    // final output too.
+    const bool tune_off = std::getenv("BLLM_TUNE_NO_THROUGH") != nullptr;
+    const bool through = p.through && !tune_off;
     ThroughArgs th;
     th.k_own = k_suffix;
     th.v_own = v_suffix;
     th.o_out = o_out;
     th.lse_out = lse_out;
+    th.pairs = through;
+    th.final_prefix_rows = p.tile_rows > 0 && p.n_rows > p.group_prefix_row_start[0] && !tune_off;
+    const bool use_th = th.pairs || th.final_prefix_rows;
     if (through && (!k_suffix || !v_suffix)) {
         set_error("null KV pointer");
         return BLLM_INVALID_ARG;
     }
-    rc = launch_pass_kernels(pg, true, q, k_prefix, v_prefix, o1, l1, MergeTarget{}, hip_stream, through ? &th : nullptr);
+    rc = launch_pass_kernels(pg, true, q, k_prefix, v_prefix, o1, l1, MergeTarget{}, hip_stream, use_th ? &th : nullptr);
     if (rc != BLLM_OK) return rc;
     // The suffix kernels fold every prefix partial of a row - one, or the pieces of a split prefix
     // straight from the split workspace, without a combine launch - with their own result.
@@ -492,7 +509,7 @@ int bllm_prefix_shared_attention(const bllm_prefix_groups* pg, const void* q, co
         mt.ws_o = pg->d.ws_o;
         mt.ws_lse = pg->d.ws_lse;
     }
-    return launch_pass_kernels(pg, false, q, k_suffix, v_suffix, nullptr, nullptr, mt, hip_stream, through ? &th : nullptr);
+    return launch_pass_kernels(pg, false, q, k_suffix, v_suffix, nullptr, nullptr, mt, hip_stream, use_th ? &th : nullptr);
 }
 
 size_t bllm_prefix_shared_single_launch_workspace_bytes(const bllm_prefix_groups* pg) {

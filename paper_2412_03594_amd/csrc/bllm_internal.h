@@ -126,6 +126,8 @@ struct MergeTarget {
 // attention in one workgroup: after the item's own range (the shared prefix) the same rows go on, with the
 // running softmax state they have, over rows [kv_row0, kv_row0 + kv_len) of (k, v) - the request's own
 // keys, causal from vis0 - and the normalised result is the final output.  kv_len == 0: no second range.
+// An item without a second range whose rows start at or after packed row final_from_row (the rows of prefixes
+// being prefilled: they have no other part) also writes the final output instead of a partial.
 struct SecondRange {
     const uint16_t* k = nullptr;
     const uint16_t* v = nullptr;
@@ -134,6 +136,7 @@ struct SecondRange {
     int32_t vis0 = 0;
     void* o_out = nullptr;         // [n_rows, Hq, D] bf16
     float* lse_out = nullptr;      // [n_rows, Hq] or null
+    int32_t final_from_row = INT32_MAX;
 };
 
 hipError_t launch_stream_attention(const LaunchCtx& c, const Item* items, int32_t n_items, int waves_per_item,
@@ -143,11 +146,12 @@ hipError_t launch_tile_attention(const LaunchCtx& c, const Item* items, int32_t 
                                  const void* k, const void* v, float* o_part, float* lse_part, float* ws_o,
                                  float* ws_lse, const MergeTarget& mt);
 // The shared-prefix tiles of a batch together with its two-range items (pairs of items: the prefix range in
-// (k, v), then the request's own range in (k2, v2)), which write rows of the final output; one launch.
+// (k, v), then the request's own range in (k2, v2)), which write rows of the final output; one launch.  Plain
+// tiles whose rows start at or after final_from_row write the final output too.
 hipError_t launch_tile_attention_through(const LaunchCtx& c, const Item* pairs, int32_t n_pairs, const Item* items,
                                          int32_t n_items, int waves, const void* q, const void* k, const void* v,
                                          const void* k2, const void* v2, float* o_part, float* lse_part, float* ws_o,
-                                         float* ws_lse, void* o_out, float* lse_out);
+                                         float* ws_lse, void* o_out, float* lse_out, int32_t final_from_row);
 // Chunk tiles and streaming items of the distinct-suffix pass as workgroups of one launch (bf16, head_dim 128,
 // both lists non-empty).
 hipError_t launch_suffix_fused(const LaunchCtx& c, const Item* tiles, int32_t n_tiles, const Item* rows, int32_t n_rows_items,

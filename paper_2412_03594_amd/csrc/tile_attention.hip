@@ -22,10 +22,14 @@ __global__ __launch_bounds__(64 * NW, 2) void tile_through_kernel(
     const Item* __restrict__ pairs, int n_pairs, const Item* __restrict__ items, const uint16_t* __restrict__ q,
     const uint16_t* __restrict__ k, const uint16_t* __restrict__ v, const uint16_t* __restrict__ k2,
     const uint16_t* __restrict__ v2, float* __restrict__ o_part, float* __restrict__ lse_part, float* __restrict__ ws_o,
-    float* __restrict__ ws_lse, int n_q_heads, int n_kv_heads, int log2_rho, float scale, void* o_out, float* lse_out) {
+    float* __restrict__ ws_lse, int n_q_heads, int n_kv_heads, int log2_rho, float scale, void* o_out, float* lse_out,
+    int final_from_row) {
     const int b = blockIdx.x;
     Item it;
     SecondRange r2;
+    r2.o_out = o_out;
+    r2.lse_out = lse_out;
+    r2.final_from_row = final_from_row;
     if (b < n_pairs) {
         it = pairs[2 * b];
         const Item own = pairs[2 * b + 1];
@@ -34,8 +38,6 @@ __global__ __launch_bounds__(64 * NW, 2) void tile_through_kernel(
         r2.kv_row0 = own.kv_row0;
         r2.kv_len = own.kv_len;
         r2.vis0 = own.vis0;
-        r2.o_out = o_out;
-        r2.lse_out = lse_out;
     } else {
         it = items[b - n_pairs];
     }
@@ -67,8 +69,8 @@ hipError_t launch_tile_attention(const LaunchCtx& c, const Item* items, int32_t 
 hipError_t launch_tile_attention_through(const LaunchCtx& c, const Item* pairs, int32_t n_pairs, const Item* items,
                                          int32_t n_items, int waves, const void* q, const void* k, const void* v,
                                          const void* k2, const void* v2, float* o_part, float* lse_part, float* ws_o,
-                                         float* ws_lse, void* o_out, float* lse_out) {
-    if (n_pairs <= 0) return hipErrorInvalidValue;
+                                         float* ws_lse, void* o_out, float* lse_out, int32_t final_from_row) {
+    if (n_pairs < 0 || n_pairs + n_items <= 0) return hipErrorInvalidValue;
     if (c.desc->dtype != BLLM_BF16 || c.desc->head_dim != kD || waves != 4 || n_items < 0) return hipErrorInvalidValue;
     const int rho = c.desc->n_q_heads / c.desc->n_kv_heads;
     int log2_rho = 0;
@@ -76,7 +78,7 @@ hipError_t launch_tile_attention_through(const LaunchCtx& c, const Item* pairs, 
     hipLaunchKernelGGL((tile_through_kernel<4, 64>), dim3(n_pairs + n_items), dim3(256), 0, c.stream, pairs, n_pairs, items,
                        static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k), static_cast<const uint16_t*>(v),
                        static_cast<const uint16_t*>(k2), static_cast<const uint16_t*>(v2), o_part, lse_part, ws_o, ws_lse,
-                       c.desc->n_q_heads, c.desc->n_kv_heads, log2_rho, c.scale, o_out, lse_out);
+                       c.desc->n_q_heads, c.desc->n_kv_heads, log2_rho, c.scale, o_out, lse_out, final_from_row);
     return hipGetLastError();
 }
 

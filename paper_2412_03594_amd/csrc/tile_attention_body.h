@@ -111,6 +111,7 @@ __device__ __forceinline__ void tile_attention_body(
     const int head0 = it.kv_head << log2_rho;
     int kv_len = it.kv_len;          // of the range being worked on
     const bool through = r2.kv_len > 0;
+    const bool final_out = through || it.q_row0 >= r2.final_from_row;    // the result is the row's final output
     const float c2 = scale * kLog2e;
 
     float* dst_o;
@@ -406,8 +407,8 @@ __device__ __forceinline__ void tile_attention_body(
 
     // ---- epilogue: normalise and store O (transposed back), log-sum-exp --------------------------
     const float ltot = l_run + __shfl_xor(l_run, 32);
-    if (through) {
-        // both parts are in the accumulators: the normalised result is the final output
+    if (final_out) {
+        // every part of these rows is in the accumulators: the normalised result is the final output
         if (row_ok) {
             const float inv = 1.f / ltot;                        // every row sees its own key
 #pragma unroll
