@@ -68,6 +68,9 @@ def algorithmic_work(batch, meta):
     pairs = meta.get("through_pair_items", np.zeros((0, 2, 8), np.int32))
     t_through = float(pairs[pairs[:, 0, 2] == 0, 0, 1].sum()) if len(pairs) else 0.0
     one_call["bytes"] -= t_through * hq * (2 * (4 * d + 4) + d * e)
+    if L.dtype == 1 and d == 128:
+        # rows of prefixes being prefilled: their tiles write the final output, no partial in between
+        one_call["bytes"] -= float(pre_g.sum()) * hq * 2 * (4 * d + 4)
     # the new K/V rows of the batch's own tokens: read once, written once, plus the destination index
     kv_append = {"bytes": float(T * (2 * 2 * hkv * d * e + 4)), "flops": 0.0}
     return {"prefix": prefix, "suffix": suffix, "merge": merge, "suffix_merged": suffix_merged, "one_call": one_call,
