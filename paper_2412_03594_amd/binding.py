@@ -80,6 +80,13 @@ def load_library():
     if not os.path.exists(path):
         from . import build
         build.build_library(verbose=False)
+    # PyTorch ships a HIP runtime of its own.  It has to be in the process before this library is, so that the
+    # library's calls go to the runtime that PyTorch's streams and allocations belong to (loaded the other way
+    # round, the library's first device call reported that there is no device).
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = C.CDLL(path)
     h = C.c_void_p
     lib.bllm_prefix_group_create.argtypes = [C.POINTER(LayerDesc), C.c_int32, _I32P, C.c_int32, _I32P, _I32P, _I32P,

@@ -527,3 +527,21 @@ def test_chunks_taken_through_both_parts_in_one_workgroup(hq, hkv):
     assert len(m["through_prefix_tile_items"]) > 0
     pg.destroy()
     check_all(b, workload.draw_values(b))
+
+
+def test_library_loaded_before_torch_in_a_fresh_process():
+    """A process whose first act is a host-only call of the library (nothing has imported torch yet) can still
+    create a device handle afterwards: the binding brings PyTorch's HIP runtime in before the library's."""
+    import os
+    import subprocess
+    import sys
+    code = ("import numpy as np, paper_2412_03594_amd as b\n"
+            "args = ((8, 2, 128, b.BF16), [5], [0, 0], [3, 4], [1, 2])\n"
+            "b.prefix_group_create(*args, host_only=True).destroy()\n"
+            "pg = b.prefix_group_create(*args)\n"
+            "assert pg.metadata()['n_rows'] == 3\n"
+            "pg.destroy()\n"
+            "print('ok')\n")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, "-c", code], cwd=root, capture_output=True, text=True, timeout=180)
+    assert r.returncode == 0 and r.stdout.strip().endswith("ok"), (r.stdout, r.stderr)
