@@ -101,7 +101,7 @@ typedef struct {
     const int32_t* suffix_row_split;   /* [T][3] same for the suffix pass */
     /* Lists of bllm_prefix_shared_attention for a batch with prefill chunks (BF16, D = 128; all empty / 0
      * otherwise).  A request whose chunk fills its own tiles - q_len >= 2 and
-     * pad * prefix_len < 400 * q_len, pad = rows missing in its last tile - is taken through both parts in
+     * pad * prefix_len < 700 * q_len, pad = rows missing in its last tile - is taken through both parts in
      * one workgroup (Sec. 4.3.3's two partial attentions reduced by the online softmax itself, Sec. 5): each
      * of its (row block, KV head) tiles is a PAIR of items, the prefix range and then the request's own
      * causal range, and no partial result exists for its rows.  The other rows keep the two-pass form, with

@@ -120,7 +120,7 @@ SPLIT_WHEN_BELOW = 512      # split prefixes when fewer tile items than this wou
 SPLIT_TARGET_ITEMS = 512
 MIN_SPLIT_LEN = 512
 KV_TILE = 64
-THROUGH_GAIN = 400          # a chunk goes through both parts in one workgroup when pad * prefix_len < this * q_len
+THROUGH_GAIN = 700          # a chunk goes through both parts in one workgroup when pad * prefix_len < this * q_len
 
 
 def _ceil_div(a, b):

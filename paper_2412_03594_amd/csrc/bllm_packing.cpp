@@ -19,7 +19,7 @@ constexpr int kSplitWhenBelow = 512;    // split the prefix when fewer tile item
 constexpr int kSplitTargetItems = 512;  // two workgroups per compute unit
 constexpr int kSingleLaunchSplitBelow = 128;   // the single launch splits prefixes when fewer tiles than this exist ...
 constexpr int kSingleLaunchTargetItems = 128;  // ... into about half a tile per compute unit
-constexpr int64_t kThroughGain = 400;         // a chunk goes through both parts in one workgroup when pad * prefix_len < this * q_len
+constexpr int64_t kThroughGain = 700;         // a chunk goes through both parts in one workgroup when pad * prefix_len < this * q_len
 constexpr int kMinSplitLen = 512;       // shorter splits cost more in partial-result traffic than they gain
 
 bool fits_i32(int64_t v) { return v >= 0 && v <= std::numeric_limits<int32_t>::max(); }
@@ -342,8 +342,10 @@ int build_packing(const bllm_layer_desc& desc, int32_t n_groups, const int32_t* 
     // pair of items: the prefix range, then the request's own causal range), which leaves no partial result to
     // write and read back; the price is the padding of the request's last row block over the prefix, which the
     // shared-prefix tiles would have filled with the next request's rows.  Taken when that padding costs less
-    // matrix-core time than the partial costs memory time: pad * prefix_len * 4 D flops a query head at about
-    // 1 PFLOP/s against q_len * 2 (4 D + 4) bytes at about 5 TB/s, i.e. pad * prefix_len < 400 * q_len.
+    // matrix-core time than the partial costs: pad * prefix_len * 4 D flops a query head at about 1 PFLOP/s
+    // against q_len * 2 (4 D + 4) bytes at about 5 TB/s gives pad * prefix_len < 400 * q_len; measured (256
+    // chunks of 24 to 144 rows, prefixes of 128 to 8192 tokens, 4 and 8 query heads per KV head) the two forms
+    // are level at 680 to 850, the partial also costing its launch tail and a second read of Q: 700.
     p.through = false;
     p.th_pair_items.clear();
     p.th_prefix_tile_items.clear();
@@ -354,12 +356,14 @@ int build_packing(const bllm_layer_desc& desc, int32_t n_groups, const int32_t* 
     if (mfma && !p.suffix_tile_items.empty()) {
         const int32_t br = p.tile_rows;
         std::vector<char> through(p.n_active, 0);
+        int64_t through_gain = kThroughGain;
+        if (const char* ov = std::getenv("BLLM_TUNE_THROUGH_GAIN")) through_gain = std::atoll(ov);
         for (int32_t a = 0; a < p.n_active; ++a) {
             const int32_t r = p.perm_req[a];
             const int32_t nq = req_q_len[r], s = req_suffix_len[r], g = req_group[r], row0 = p.req_row_start[a];
             if (nq < 2) continue;
             const int64_t pad = static_cast<int64_t>(ceil_div(nq, br)) * br - nq;
-            if (pad * prefix_len[g] < kThroughGain * static_cast<int64_t>(nq)) {
+            if (pad * prefix_len[g] < through_gain * static_cast<int64_t>(nq)) {
                 through[a] = 1;
                 p.through = true;
                 for (int32_t i0 = 0; i0 < nq; i0 += br) {

@@ -245,38 +245,38 @@ def test_one_call_workspace_tells_which_form_runs():
 def test_through_lists_hand_case():
     """Which prefill chunks go through both parts in one workgroup, on a batch small enough to write the
     lists out by hand.  Hq 8, Hkv 2: 32 token rows per tile.  Group 0 (prefix 1000): a 64-row chunk (no
-    padding: through), a 40-row chunk (24 padded rows x 1000 >= 400 x 40: stays two-pass), a decode row;
-    group 1 (prefix 10): a 33-row chunk (31 x 10 < 400 x 33: through)."""
+    padding: through), a 34-row chunk (30 padded rows x 1000 >= 700 x 34: stays two-pass), a decode row;
+    group 1 (prefix 10): a 33-row chunk (31 x 10 < 700 x 33: through)."""
     L = workload.Layer(8, 2, 128, workload.BF16)
     b = workload.Batch("hand", L, np.array([1000, 10], np.int32), np.array([0, 0, 0, 1], np.int32),
-                       np.array([100, 50, 7, 33], np.int32), np.array([64, 40, 1, 33], np.int32))
+                       np.array([100, 44, 7, 33], np.int32), np.array([64, 34, 1, 33], np.int32))
     m = check_work_lists(b)
     assert m["tile_rows"] == 32
-    # packed order: group 0: the decode row (row 0), the 64-row chunk (rows 1..64), the 40-row chunk (65..104);
-    # group 1: the 33-row chunk (105..137).  Suffix KV rows: 0.., 100.., 150.., 157..
+    # packed order: group 0: the decode row (row 0), the 64-row chunk (rows 1..64), the 34-row chunk (65..98);
+    # group 1: the 33-row chunk (99..131).  Suffix KV rows: 0.., 100.., 144.., 151..
     assert list(m["perm_req"]) == [2, 0, 1, 3]
     pairs = [[list(a), list(c)] for a, c in m["through_pair_items"]]
     want = []
     for i0, n, vis0 in ((1, 32, 37), (33, 32, 69)):                       # positions 36..67 and 68..99 of request 0
         for j in (0, 1):
             want.append([[i0, n, j, 0, 1000, 1000, -1, 0], [i0, n, j, 0, vis0 + n - 1, vis0, -1, 0]])
-    for i0, n, vis0 in ((105, 32, 1), (137, 1, 33)):                      # request 3 starts at position 0
+    for i0, n, vis0 in ((99, 32, 1), (131, 1, 33)):                       # request 3 starts at position 0
         for j in (0, 1):
-            want.append([[i0, n, j, 1000, 10, 10, -1, 0], [i0, n, j, 157, vis0 + n - 1, vis0, -1, 0]])
+            want.append([[i0, n, j, 1000, 10, 10, -1, 0], [i0, n, j, 151, vis0 + n - 1, vis0, -1, 0]])
     assert pairs == want
-    # what is left for the two passes: the decode row and the 40-row chunk.  They are two runs of rows (the
+    # what is left for the two passes: the decode row and the 34-row chunk.  They are two runs of rows (the
     # through request lies between them); with 8 pairs there are 8 + 2 + 4 = 14 < 512 tiles, so the prefix is
     # split into 512-row pieces.
     pt = [list(x) for x in m["through_prefix_tile_items"]]
     assert sorted(pt) == sorted(
         [[0, 1, j, 0, 512, 512, 0, 0] for j in (0, 1)] + [[0, 1, j, 512, 488, 488, 1, 0] for j in (0, 1)] +
-        [[65 + i0, n, j, off, ln, ln, 2 + c * 40 + i0, 0] for c, (off, ln) in enumerate(((0, 512), (512, 488)))
-         for i0, n in ((0, 32), (32, 8)) for j in (0, 1)])
-    assert m["n_through_prefix_ws_rows"] == 2 + 80
-    assert [list(x) for x in m["through_prefix_row_split"][[0, 1, 65, 104, 105]]] == \
-        [[0, 1, 2], [0, 0, 0], [2, 40, 2], [41, 40, 2], [0, 0, 0]]
+        [[65 + i0, n, j, off, ln, ln, 2 + c * 34 + i0, 0] for c, (off, ln) in enumerate(((0, 512), (512, 488)))
+         for i0, n in ((0, 32), (32, 2)) for j in (0, 1)])
+    assert m["n_through_prefix_ws_rows"] == 2 + 68
+    assert [list(x) for x in m["through_prefix_row_split"][[0, 1, 65, 98, 99]]] == \
+        [[0, 1, 2], [0, 0, 0], [2, 34, 2], [35, 34, 2], [0, 0, 0]]
     assert [list(x) for x in m["through_suffix_tile_items"]] == \
-        [[65 + i0, n, j, 100, 10 + i0 + n, 10 + i0 + 1, -1, 0] for i0, n in ((0, 32), (32, 8)) for j in (0, 1)]
+        [[65 + i0, n, j, 100, 10 + i0 + n, 10 + i0 + 1, -1, 0] for i0, n in ((0, 32), (32, 2)) for j in (0, 1)]
 
 
 @pytest.mark.parametrize("seed", range(10))
