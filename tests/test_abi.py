@@ -325,3 +325,17 @@ def test_through_lists_cover_every_row_head_once(seed):
     for a in range(m["n_active"]):
         rows = in_pair[m["req_row_start"][a]:m["req_row_start"][a + 1]]
         assert rows.all() or not rows.any()
+
+
+def test_through_threshold_tuning_hook(monkeypatch):
+    """BLLM_TUNE_THROUGH_GAIN replaces the 700 of the rule at create: 0 takes no chunk through both parts in one
+    workgroup (only chunks without padding over an empty prefix would pass 0 < 0), a huge value takes every chunk."""
+    L = workload.Layer(8, 2, 128, workload.BF16)
+    b = workload.Batch("hook", L, np.array([1000], np.int32), np.array([0, 0, 0], np.int32),
+                       np.array([100, 44, 7], np.int32), np.array([64, 34, 1], np.int32))
+    n_pairs = lambda: len(host_pack(b).metadata()["through_pair_items"])
+    assert n_pairs() == 4                       # the 64-row chunk: 2 row blocks x 2 KV heads
+    monkeypatch.setenv("BLLM_TUNE_THROUGH_GAIN", "0")
+    assert n_pairs() == 0
+    monkeypatch.setenv("BLLM_TUNE_THROUGH_GAIN", "1000000")
+    assert n_pairs() == 4 + 4                   # and the 34-row chunk
