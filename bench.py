@@ -379,6 +379,66 @@ def token_batching_job(bllm, with_oracle):
     return out
 
 
+def job_attention(bllm, torch, n_groups, s_chunk=2048, m_threshold=400000):
+    """Attention of ONE layer over every iteration of a whole synthetic job shaped like the paper's offline
+    workloads (the job of token_batching_job, n_groups groups of 3 requests): the library's token batching forms
+    each batch (Sec. 3.3), a handle is created for it, the batch's new K/V rows are appended and the one-call
+    attention runs.  K/V contents are random (only the shapes matter for time); all device buffers are allocated
+    once.  Reports GPU time (events around the two device calls of every iteration) and wall-clock time, which
+    also holds the host's batching, packing and upload."""
+    import workload
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(1)
+    prefix_len = rng.integers(1200, 1900, n_groups)
+    req_group = np.repeat(np.arange(n_groups), 3)
+    distinct = rng.integers(10, 60, req_group.shape[0])
+    decode = rng.integers(96, 160, req_group.shape[0])
+    L = workload.Layer(32, 8, 128, workload.BF16)
+    desc = (L.n_q_heads, L.n_kv_heads, L.head_dim, L.dtype)
+    max_rows = 2 * s_chunk + 4096
+    kv_rows = m_threshold + 2 * s_chunk
+    g = torch.Generator(device=dev)
+    g.manual_seed(0)
+    mk = lambda n, h: torch.randn((n, h, L.head_dim), device=dev, dtype=torch.bfloat16, generator=g)
+    q, k_new, v_new = mk(max_rows, L.n_q_heads), mk(max_rows, L.n_kv_heads), mk(max_rows, L.n_kv_heads)
+    kp, vp, ks, vs = (mk(kv_rows, L.n_kv_heads) for _ in range(4))
+    o = torch.empty((max_rows, L.n_q_heads, L.head_dim), device=dev, dtype=torch.bfloat16)
+    ws = torch.empty(2 * max_rows * L.n_q_heads * (L.head_dim + 1) + 1024, device=dev, dtype=torch.float32)
+    job = bllm.Job(prefix_len, req_group, distinct, decode, s_chunk, m_threshold)
+    events, tokens, kinds = [], 0, {"one launch": 0, "two phases": 0}
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    while True:
+        b = job.next_batch()
+        if b is None:
+            break
+        pg = bllm.prefix_group_create(desc, b["prefix_len"], b["req_group"], b["req_suffix_len"], b["req_q_len"],
+                                      prefix_q_len=b["prefix_q_len"])
+        T = b["n_decode_tokens"] + b["n_distinct_tokens"] + b["n_prefix_tokens"]
+        need = bllm.prefix_shared_workspace_bytes(pg)
+        assert T <= max_rows and need <= ws.numel() * 4 and sum(b["prefix_len"]) <= kv_rows and sum(b["req_suffix_len"]) <= kv_rows
+        kinds["one launch" if need == bllm.prefix_shared_single_launch_workspace_bytes(pg) and T > 0 else "two phases"] += 1
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        bllm.kv_append(pg, k_new, v_new, kp, vp, ks, vs)
+        bllm.prefix_shared_attention(pg, q, kp, vp, ks, vs, ws, o, None)
+        e1.record()
+        events.append((e0, e1))
+        tokens += T
+        pg.destroy()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    gpu_ms = sum(a.elapsed_time(c) for a, c in events)
+    job.destroy()
+    return {"metric": "attention tokens/s per layer over a whole job", "value": round(tokens / (gpu_ms * 1e-3), 1),
+            "unit": "tokens/s", "n_gpus": 1, "higher_is_better": True, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": "job: %d groups x 3 requests, prefix U[1200,1900), distinct U[10,60), output U[96,160); "
+                                   "S_chunk %d, M_threshold %d KV tokens; Llama-3-8B-shaped layer" % (n_groups, s_chunk, m_threshold)},
+            "iterations": len(events), "tokens": int(tokens), "gpu_ms": round(gpu_ms, 2),
+            "gpu_us_per_iteration": round(gpu_ms * 1e3 / max(len(events), 1), 1), "wall_ms": round(wall * 1e3, 1),
+            "one_call_runs_as": kinds}
+
+
 def roofline_of(res):
     """Roofline record of the pass that takes the most time."""
     t = res["t_pass"]
@@ -438,6 +498,10 @@ def main():
     ap.add_argument("--device-values", action="store_true",
                     help="draw the main workload's Q/K/V on the device (for the workloads whose KV takes minutes to "
                          "draw on the host); implies --no-cpu-baseline, which needs the values on the host")
+    ap.add_argument("--job-groups", type=int, default=0,
+                    help="instead of one batch: attention of one layer over every iteration of a whole synthetic job "
+                         "of this many prefix-sharing groups (token batching, packing, KV append and the one-call "
+                         "attention per iteration); prints its own JSON line")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device-to-device copy (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -447,6 +511,10 @@ def main():
         sys.exit(2)
 
     import torch
+    if args.job_groups > 0:
+        import paper_2412_03594_amd as bllm_job
+        print(json.dumps(job_attention(bllm_job, torch, args.job_groups)))
+        return
     import workload
     import paper_2412_03594_amd as bllm
     if not torch.cuda.is_available():

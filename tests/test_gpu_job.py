@@ -60,3 +60,18 @@ def test_job_end_to_end(dtype, hq, hkv, d, s_chunk, m):
         n_it += 1
     assert tokens == sum(prefix_len) + sum(distinct) + sum(decode) - len(decode)
     job.destroy()
+
+
+def test_bench_job_mode_runs_a_small_job():
+    """bench.py --job-groups: every iteration of a small job through token batching, packing, KV append and the
+    one-call attention; the token count is the job's."""
+    import torch
+    import bench
+    import paper_2412_03594_amd as bllm
+    out = bench.job_attention(bllm, torch, 6, s_chunk=512, m_threshold=40000)
+    rng = np.random.default_rng(1)
+    prefix_len = rng.integers(1200, 1900, 6)
+    distinct = rng.integers(10, 60, 18)
+    decode = rng.integers(96, 160, 18)
+    assert out["tokens"] == int(prefix_len.sum() + distinct.sum() + decode.sum() - 18)
+    assert out["iterations"] > 0 and out["gpu_ms"] > 0 and out["value"] > 0
