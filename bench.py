@@ -384,8 +384,9 @@ def job_attention(bllm, torch, n_groups, s_chunk=2048, m_threshold=400000):
     workloads (the job of token_batching_job, n_groups groups of 3 requests): the library's token batching forms
     each batch (Sec. 3.3), a handle is created for it, the batch's new K/V rows are appended and the one-call
     attention runs.  K/V contents are random (only the shapes matter for time); all device buffers are allocated
-    once.  Reports GPU time (events around the two device calls of every iteration) and wall-clock time, which
-    also holds the host's batching, packing and upload."""
+    once.  The host's part (batching, packing, upload of every iteration's handle) runs first and is reported in
+    wall-clock time; then the device calls of all iterations are issued back to back, once to warm up and once
+    between two events: the GPU time of the job's attention."""
     import workload
     dev = torch.device("cuda:0")
     rng = np.random.default_rng(1)
@@ -405,8 +406,8 @@ def job_attention(bllm, torch, n_groups, s_chunk=2048, m_threshold=400000):
     o = torch.empty((max_rows, L.n_q_heads, L.head_dim), device=dev, dtype=torch.bfloat16)
     ws = torch.empty(2 * max_rows * L.n_q_heads * (L.head_dim + 1) + 1024, device=dev, dtype=torch.float32)
     job = bllm.Job(prefix_len, req_group, distinct, decode, s_chunk, m_threshold)
-    events, tokens, kinds = [], 0, {"one launch": 0, "two phases": 0}
-    torch.cuda.synchronize()
+    handles, tokens, kinds = [], 0, {"one launch": 0, "two phases": 0}
+    # the host's part first (token batching, packing, upload), so that the timed loop below keeps the GPU busy
     t0 = time.perf_counter()
     while True:
         b = job.next_batch()
@@ -418,25 +419,35 @@ def job_attention(bllm, torch, n_groups, s_chunk=2048, m_threshold=400000):
         need = bllm.prefix_shared_workspace_bytes(pg)
         assert T <= max_rows and need <= ws.numel() * 4 and sum(b["prefix_len"]) <= kv_rows and sum(b["req_suffix_len"]) <= kv_rows
         kinds["one launch" if need == bllm.prefix_shared_single_launch_workspace_bytes(pg) and T > 0 else "two phases"] += 1
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        bllm.kv_append(pg, k_new, v_new, kp, vp, ks, vs)
-        bllm.prefix_shared_attention(pg, q, kp, vp, ks, vs, ws, o, None)
-        e1.record()
-        events.append((e0, e1))
+        handles.append(pg)
         tokens += T
-        pg.destroy()
+    host = time.perf_counter() - t0
+    job.destroy()
+
+    def run_all():
+        for pg in handles:
+            bllm.kv_append(pg, k_new, v_new, kp, vp, ks, vs)
+            bllm.prefix_shared_attention(pg, q, kp, vp, ks, vs, ws, o, None)
+    run_all()                                   # warm-up pass over the whole job
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    run_all()
+    e1.record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    gpu_ms = sum(a.elapsed_time(c) for a, c in events)
-    job.destroy()
+    gpu_ms = e0.elapsed_time(e1)
+    n_it = len(handles)
+    for pg in handles:
+        pg.destroy()
     return {"metric": "attention tokens/s per layer over a whole job", "value": round(tokens / (gpu_ms * 1e-3), 1),
             "unit": "tokens/s", "n_gpus": 1, "higher_is_better": True, "dtype": "bf16", "data": "synthetic",
             "config": {"workload": "job: %d groups x 3 requests, prefix U[1200,1900), distinct U[10,60), output U[96,160); "
                                    "S_chunk %d, M_threshold %d KV tokens; Llama-3-8B-shaped layer" % (n_groups, s_chunk, m_threshold)},
-            "iterations": len(events), "tokens": int(tokens), "gpu_ms": round(gpu_ms, 2),
-            "gpu_us_per_iteration": round(gpu_ms * 1e3 / max(len(events), 1), 1), "wall_ms": round(wall * 1e3, 1),
-            "one_call_runs_as": kinds}
+            "iterations": n_it, "tokens": int(tokens), "gpu_ms": round(gpu_ms, 2),
+            "gpu_us_per_iteration": round(gpu_ms * 1e3 / max(n_it, 1), 1), "launch_loop_wall_ms": round(wall * 1e3, 1),
+            "host_batching_packing_upload_ms": round(host * 1e3, 1), "one_call_runs_as": kinds}
 
 
 def roofline_of(res):

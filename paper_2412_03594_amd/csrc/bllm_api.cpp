@@ -439,9 +439,10 @@ int bllm_kv_append(const bllm_prefix_groups* pg, const void* k_new, const void* 
 // prefill-chunk tiles (whose fp32 partials would make the early parts' round trip expensive).
 // l8b_decode: 80.2 us against 83.9 us per step; 256 decode rows on one 2048-token prefix: 72.7 against 77.6 us.
 // Measured the other way: 32 decode rows on one prefix (41 against 27 us), 512 prefix tiles (220 against 217 us).
+// Also one launch: decode-only batches of many small groups (the rule and its measurements are in the packing code).
 static bool one_call_uses_single_launch(const bllm_prefix_groups* pg) {
     const Packing& p = pg->pk;
-    return p.single_launch && std::getenv("BLLM_TUNE_ONE_CALL_TWO_PHASE") == nullptr;
+    return (p.single_launch || p.single_launch_sparse) && std::getenv("BLLM_TUNE_ONE_CALL_TWO_PHASE") == nullptr;
 }
 
 // bytes of one fp32 partial result (O, L) of the whole batch

@@ -43,6 +43,8 @@ struct Packing {
     bool prefix_has_split = false, suffix_has_split = false;
     // prefix tiles of the single-launch form (fewer, longer pieces), when the batch qualifies for it
     bool single_launch = false, sl_prefix_has_split = false;
+    // one launch too, with the prefix tiles of the separate pass: decode-only batches of many small groups
+    bool single_launch_sparse = false;
     std::vector<Item> sl_prefix_tile_items;
     std::vector<RowSplit> sl_prefix_row_split;
     int32_t n_sl_prefix_ws_rows = 0;

@@ -240,6 +240,20 @@ def test_one_call_workspace_tells_which_form_runs():
     pg = host_pack(b)
     assert 2 * bllm.prefix_shared_workspace_bytes(pg) == bllm.prefix_shared_single_launch_workspace_bytes(pg)
     pg.destroy()
+    # decode-only batches of many small groups (at most 8 token rows per prefix tile on average) are one launch too
+    L = workload.Layer(32, 8, 128, workload.BF16)
+    for groups, rows, one_launch in ((64, 3, True), (5, 8, True), (5, 9, False), (1, 32, False)):
+        b = workload.Batch("sparse", L, np.full(groups, 1500, np.int32), np.repeat(np.arange(groups), rows).astype(np.int32),
+                           np.full(groups * rows, 100, np.int32), np.ones(groups * rows, np.int32))
+        pg = host_pack(b)
+        ratio = bllm.prefix_shared_single_launch_workspace_bytes(pg) // bllm.prefix_shared_workspace_bytes(pg)
+        assert ratio == (1 if one_launch else 2), (groups, rows)
+        pg.destroy()
+    b = workload.Batch("sparse+chunk", L, np.full(4, 1500, np.int32), np.arange(4).astype(np.int32),
+                       np.array([100, 100, 100, 100], np.int32), np.array([1, 1, 1, 40], np.int32))
+    pg = host_pack(b)
+    assert 2 * bllm.prefix_shared_workspace_bytes(pg) == bllm.prefix_shared_single_launch_workspace_bytes(pg)
+    pg.destroy()
 
 
 def test_through_lists_hand_case():

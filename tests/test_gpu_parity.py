@@ -219,12 +219,13 @@ def test_many_prefix_splits_folded_in_the_suffix_epilogue(suffixes):
 def test_one_call_rejects_a_small_or_misaligned_workspace():
     import torch
     import paper_2412_03594_amd as bllm
-    pg = bllm.prefix_group_create((8, 2, 128, workload.BF16, 0.0), [5], [0], [3], [1])
+    # a prefill chunk of 2 rows: a batch that the one-call entry point runs as prefix kernels, then suffix kernels
+    pg = bllm.prefix_group_create((8, 2, 128, workload.BF16, 0.0), [5], [0], [3], [2])
     need = bllm.prefix_shared_workspace_bytes(pg)
-    assert need >= 8 * 129 * 4
+    assert need >= 2 * 8 * 129 * 4
     dev = torch.device("cuda:0")
     t = lambda *shape, dt=torch.bfloat16: torch.zeros(shape, device=dev, dtype=dt)
-    q, kp, ks, o = t(1, 8, 128), t(5, 2, 128), t(3, 2, 128), t(1, 8, 128)
+    q, kp, ks, o = t(2, 8, 128), t(5, 2, 128), t(3, 2, 128), t(2, 8, 128)
     small = torch.zeros(need // 4 - 1, device=dev, dtype=torch.float32)
     with pytest.raises(bllm.BllmError):
         bllm.prefix_shared_attention(pg, q, kp, kp, ks, ks, small, o)
