@@ -277,7 +277,8 @@ int bllm_kv_append(const bllm_prefix_groups* pg, const void* k_new, const void* 
  * part, are written as final output by their shared-prefix tiles likewise.  For batches
  * where it measured faster (bf16, head_dim 128, up to 4 query heads per KV head, a
  * prefix that was split along KV to fill the chip into at most 256 tiles, at least
- * 1024 streaming items, decode rows only) the call
+ * 1024 streaming items, decode rows only; or decode rows only in many small
+ * groups, on average at most 8 token rows per shared-prefix tile) the call
  * runs as bllm_prefix_shared_attention_single_launch; there the part that
  * finishes last reduces a row, so two calls on the same inputs may differ in the
  * last bit of the output's rounding.
