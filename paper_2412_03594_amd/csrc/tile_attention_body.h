@@ -175,6 +175,7 @@ __device__ __forceinline__ void tile_attention_body(
 
     // smallest visible count among this wavefront's rows: tiles that end below it need no mask
     const int wave_tok_lo = (32 * wave) >> log2_rho;
+    const bool wave_has_rows = wave_tok_lo < it.n_rows;
     int wave_min_vis = wave_tok_lo < it.n_rows ? min(kv_len, it.vis0 + wave_tok_lo) : kv_len;
 
     // ---- Q fragments (B operand of S^T = K Q^T): Q[query = col][d = 16 t + 8 h + 0..7] -------
@@ -383,10 +384,28 @@ __device__ __forceinline__ void tile_attention_body(
         wait_vector_memory<0>();
         __syncthreads();
     };
-    for (int tile = 0; tile < n_tiles; tile += 2) {
-        step(tile, smem_even, smem_odd);
-        if (tile + 1 < n_tiles) step(tile + 1, smem_odd, smem_even);
-    }
+    // A wavefront whose 32 stacked rows are all padding (a group with few rows) only moves its share of the next
+    // tile and keeps the barriers: the workgroup then steps as fast as its busy wavefronts.  It has a loop of
+    // its own, so that the step of the busy wavefronts stays the straight-line code it was.
+    auto idle_step = [&](int tile, unsigned char* sb_next) {
+        if (tile + 1 < n_tiles) dma_tile(tile + 1, sb_next);
+        wait_vector_memory<0>();
+        __syncthreads();
+    };
+    auto run_tiles = [&]() {
+        if (wave_has_rows) {
+            for (int tile = 0; tile < n_tiles; tile += 2) {
+                step(tile, smem_even, smem_odd);
+                if (tile + 1 < n_tiles) step(tile + 1, smem_odd, smem_even);
+            }
+        } else {
+            for (int tile = 0; tile < n_tiles; tile += 2) {
+                idle_step(tile, smem_odd);
+                if (tile + 1 < n_tiles) idle_step(tile + 1, smem_even);
+            }
+        }
+    };
+    run_tiles();
     if (through) {
         // The same rows go on over their second range with the running state they have: the online softmax
         // is the reduction of the two parts.  Both buffers are free (the last step ended with a barrier).
@@ -399,10 +418,7 @@ __device__ __forceinline__ void tile_attention_body(
         dma_tile(0, smem_even);
         wait_vector_memory<0>();
         __syncthreads();
-        for (int tile = 0; tile < n_tiles; tile += 2) {
-            step(tile, smem_even, smem_odd);
-            if (tile + 1 < n_tiles) step(tile + 1, smem_odd, smem_even);
-        }
+        run_tiles();
     }
 
     // ---- epilogue: normalise and store O (transposed back), log-sum-exp --------------------------
