@@ -312,7 +312,7 @@ class Job:
         _check(load_library().bllm_job_next_batch(self._h, C.byref(b), C.byref(done)))
         if done.value:
             return None
-        arr = lambda p, n: [int(p[i]) for i in range(n)]
+        arr = lambda p, n: np.ctypeslib.as_array(p, shape=(n,)).tolist() if n > 0 else []
         g, r = b.n_groups, b.n_requests
         return {"iteration": b.iteration, "groups": arr(b.groups, g), "prefix_len": arr(b.prefix_len, g),
                 "prefix_q_len": arr(b.prefix_q_len, g), "requests": arr(b.requests, r), "req_group": arr(b.req_group, r),
