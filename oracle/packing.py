@@ -215,8 +215,19 @@ def build_work_lists(meta, prefix_len, req_suffix_len, req_q_len, n_q_heads, n_k
                         for j in range(n_kv_heads):
                             tiles.append([row0 + i0, min(br, rows - i0), j, pks[g] + kv_off, kv_len, kv_len,
                                           (ws_base + c * rows + i0) if n_sp > 1 else -1, 0])
-        # longest KV range first (stable)
+        # longest KV range first (stable); then the tiles of prefix rows spread evenly among the others, each
+        # kind in its order: before output position k, at most ceil(k * share) tiles of prefix rows
         tiles.sort(key=lambda it: -it[4])
+        pre = [it for it in tiles if it[0] >= gprs[0]]
+        req = [it for it in tiles if it[0] < gprs[0]]
+        if pre and req:
+            tiles, n_pre = [], 0
+            for k in range(len(pre) + len(req)):
+                if n_pre < len(pre) and (k - n_pre >= len(req) or n_pre * (len(pre) + len(req)) <= k * len(pre)):
+                    tiles.append(pre[n_pre])
+                    n_pre += 1
+                else:
+                    tiles.append(req[k - n_pre])
         return tiles, row_split, ln_split, n_ws
 
     if mfma:

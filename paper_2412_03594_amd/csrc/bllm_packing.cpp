@@ -268,6 +268,24 @@ int build_packing(const bllm_layer_desc& desc, int32_t n_groups, const int32_t* 
         // longest KV range first (stable: the items of a group stay together and keep sharing its K/V in
         // L2, the KV heads of one row block stay adjacent)
         std::stable_sort(out.items->begin(), out.items->end(), [](const Item& a, const Item& b) { return a.kv_len > b.kv_len; });
+        // The tiles of prefix rows (causal, full of rows: bound by the matrix cores) are then spread evenly among
+        // the tiles of request rows (in decode batches a few rows against a whole prefix: bound by memory), each
+        // kind keeping its order, so that both kinds of work are in flight during the whole launch instead of the
+        // short causal tiles forming its tail (the job of 300 groups: 71.7 against 74.2 ms).
+        {
+            std::vector<Item> pre, req;
+            for (const Item& it : *out.items) (it.q_row0 >= n_request_rows ? pre : req).push_back(it);
+            if (!pre.empty() && !req.empty()) {
+                out.items->clear();
+                size_t ip = 0, ir = 0;
+                const size_t total = pre.size() + req.size();
+                for (size_t k = 0; k < total; ++k) {
+                    // keep the share of prefix-row items emitted so far at their share of the whole list
+                    const bool take_pre = ip < pre.size() && (ir >= req.size() || ip * total <= k * pre.size());
+                    out.items->push_back(take_pre ? pre[ip++] : req[ir++]);
+                }
+            }
+        }
         return BLLM_OK;
     };
 
