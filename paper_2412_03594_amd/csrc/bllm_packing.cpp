@@ -353,8 +353,10 @@ int build_packing(const bllm_layer_desc& desc, int32_t n_groups, const int32_t* 
     // first (K/V reuse between the row blocks of one request).
     finish_stream_list(p.prefix_row_items, &p.prefix_stream_wpi);
     finish_stream_list(p.suffix_row_items, &p.suffix_stream_wpi);
-    // A second list of prefix tiles for the whole path as ONE launch (decode-dominated batches: no prefill
-    // chunks, enough streaming items to fill the chip beside the tiles, up to 4 query heads per KV head).
+    // A second list of prefix tiles for the whole path as ONE launch (decode batches: no prefill chunks, no rows
+    // of prefixes being prefilled - in two phases their tiles write the final output themselves, in the single
+    // launch they would go through a partial: 260 against 241 us on the decode + prefix-chunk iterations of a
+    // job - enough streaming items to fill the chip beside the tiles, up to 4 query heads per KV head).
     // There the tiles share the compute units with the streaming items from the start, and half a tile per
     // compute unit measured best (l8b_decode: 2 pieces 74.8 us, 3 pieces 75.9, 4 pieces 77.8, unsplit 98.9).
     // Requests with prefill chunks whose rows fill their own tiles go through both parts in one workgroup (a
@@ -415,7 +417,7 @@ int build_packing(const bllm_layer_desc& desc, int32_t n_groups, const int32_t* 
         }
     }
     p.single_launch = false;
-    if (mfma && rho <= 4 && p.suffix_tile_items.empty() && p.suffix_row_items.size() >= 1024) {
+    if (mfma && rho <= 4 && p.suffix_tile_items.empty() && p.suffix_row_items.size() >= 1024 && p.n_rows == n_request_rows) {
         int32_t split_len = 0;
         const int rc = build_prefix_tiles(kSingleLaunchSplitBelow, kSingleLaunchTargetItems,
                                           PrefixTiles{&p.sl_prefix_tile_items, &p.sl_prefix_row_split, &split_len,
