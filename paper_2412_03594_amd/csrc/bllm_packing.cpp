@@ -27,6 +27,30 @@ bool fits_i32(int64_t v) { return v >= 0 && v <= std::numeric_limits<int32_t>::m
 
 int32_t ceil_div(int32_t a, int32_t b) { return (a + b - 1) / b; }
 
+// Stable sort of items by descending key.  Keys are KV lengths, so a counting sort over them is a few passes
+// over the list; very long ranges fall back to the comparison sort.  Both give the same order.
+template <typename KeyFn>
+void sort_longest_first(std::vector<Item>& v, KeyFn key) {
+    if (v.size() < 2) return;
+    int32_t max_key = 0;
+    for (const Item& it : v) max_key = std::max(max_key, key(it));
+    if (max_key > (1 << 18)) {
+        std::stable_sort(v.begin(), v.end(), [&](const Item& a, const Item& b) { return key(a) > key(b); });
+        return;
+    }
+    std::vector<int32_t> first(static_cast<size_t>(max_key) + 2, 0);     // first[k]: items with a key above k
+    for (const Item& it : v) ++first[std::max(key(it), 0)];
+    int32_t above = 0;
+    for (int32_t k = max_key; k >= 0; --k) {
+        const int32_t n = first[k];
+        first[k] = above;
+        above += n;
+    }
+    std::vector<Item> sorted(v.size());
+    for (const Item& it : v) sorted[first[std::max(key(it), 0)]++] = it;
+    v.swap(sorted);
+}
+
 }  // namespace
 
 int build_packing(const bllm_layer_desc& desc, int32_t n_groups, const int32_t* prefix_len,
@@ -177,21 +201,24 @@ int build_packing(const bllm_layer_desc& desc, int32_t n_groups, const int32_t* 
     // Runs of consecutive packed rows of group g that the shared-prefix tiles cover: the whole group, or what
     // is left of it between the requests flagged in `skip` (indexed by packed request).
     struct Run { int32_t row0, rows; };
-    auto group_runs = [&](int32_t g, const std::vector<char>* skip) {
-        std::vector<Run> runs;
+    auto for_each_run = [&](int32_t g, const std::vector<char>* skip, auto&& fn) {
+        if (skip == nullptr) {
+            const Run whole{p.group_row_start[g], p.group_row_start[g + 1] - p.group_row_start[g]};
+            if (whole.rows > 0) fn(whole);
+            return;
+        }
         Run cur{0, 0};
         for (int32_t a = p.group_req_start[g]; a < p.group_req_start[g + 1]; ++a) {
             const int32_t row0 = p.req_row_start[a], n = p.req_row_start[a + 1] - row0;
-            if (skip != nullptr && (*skip)[a]) {
-                if (cur.rows > 0) runs.push_back(cur);
+            if ((*skip)[a]) {
+                if (cur.rows > 0) fn(cur);
                 cur = Run{0, 0};
             } else {
                 if (cur.rows == 0) cur.row0 = row0;
                 cur.rows += n;
             }
         }
-        if (cur.rows > 0) runs.push_back(cur);
-        return runs;
+        if (cur.rows > 0) fn(cur);
     };
     auto build_prefix_tiles = [&](int split_when_below, int target_items, const PrefixTiles& out,
                                   const std::vector<char>* skip = nullptr, int64_t other_items = 0) -> int {
@@ -201,10 +228,10 @@ int build_packing(const bllm_layer_desc& desc, int32_t n_groups, const int32_t* 
         for (int32_t g = 0; g < n_groups; ++g) {
             base_items += static_cast<int64_t>(ceil_div(p.group_prefix_row_start[g + 1] - p.group_prefix_row_start[g], br)) * n_kv_heads;
             if (prefix_len[g] == 0) continue;
-            for (const Run& run : group_runs(g, skip)) {
+            for_each_run(g, skip, [&](const Run& run) {
                 base_items += static_cast<int64_t>(ceil_div(run.rows, br)) * n_kv_heads;
                 max_lp = std::max(max_lp, prefix_len[g]);
-            }
+            });
         }
         *out.split_len = 0;
         if (base_items > 0 && base_items < split_when_below) {
@@ -218,6 +245,7 @@ int build_packing(const bllm_layer_desc& desc, int32_t n_groups, const int32_t* 
         out.row_split->assign(p.n_rows, RowSplit{0, 0, 0});
         *out.has_split = false;
         int64_t ws_rows = 0;
+        bool ws_overflow = false;
         for (int32_t g = 0; g < n_groups; ++g) {
             // Prefix rows: causal inside the prefix (row i sees the positions up to its own),
             // never split, written directly.
@@ -229,7 +257,8 @@ int build_packing(const bllm_layer_desc& desc, int32_t n_groups, const int32_t* 
                 for (int32_t j = 0; j < n_kv_heads; ++j)
                     out.items->push_back(Item{prow0 + i0, n, j, p.prefix_kv_start[g], first_vis + n - 1, first_vis, -1, 0});
             }
-            for (const Run& run : group_runs(g, skip)) {
+            for_each_run(g, skip, [&](const Run& run) {
+            if (ws_overflow) return;
             const int32_t row0 = run.row0;
             const int32_t rows = run.rows;
             const int32_t lp = prefix_len[g];
@@ -238,8 +267,8 @@ int build_packing(const bllm_layer_desc& desc, int32_t n_groups, const int32_t* 
             if (n_sp > 1) {
                 ws_rows += static_cast<int64_t>(rows) * n_sp;
                 if (!fits_i32(ws_rows * desc.n_q_heads)) {
-                    set_error("prefix split workspace overflows int32 rows");
-                    return BLLM_INVALID_ARG;
+                    ws_overflow = true;
+                    return;
                 }
                 for (int32_t i = 0; i < rows; ++i) (*out.row_split)[row0 + i] = RowSplit{ws_base + i, rows, n_sp};
                 *out.has_split = true;
@@ -262,12 +291,16 @@ int build_packing(const bllm_layer_desc& desc, int32_t n_groups, const int32_t* 
                     }
                 }
             }
+            });
+            if (ws_overflow) {
+                set_error("prefix split workspace overflows int32 rows");
+                return BLLM_INVALID_ARG;
             }
         }
         *out.ws_rows = static_cast<int32_t>(ws_rows);
         // longest KV range first (stable: the items of a group stay together and keep sharing its K/V in
         // L2, the KV heads of one row block stay adjacent)
-        std::stable_sort(out.items->begin(), out.items->end(), [](const Item& a, const Item& b) { return a.kv_len > b.kv_len; });
+        sort_longest_first(*out.items, [](const Item& it) { return it.kv_len; });
         // The tiles of prefix rows (causal, full of rows: bound by the matrix cores) are then spread evenly among
         // the tiles of request rows (in decode batches a few rows against a whole prefix: bound by memory), each
         // kind keeping its order, so that both kinds of work are in flight during the whole launch instead of the
@@ -337,9 +370,7 @@ int build_packing(const bllm_layer_desc& desc, int32_t n_groups, const int32_t* 
     // Streaming items: longest first, so that the hardware's in-order workgroup dispatch
     // balances the ragged lengths; then pick how many wavefronts share an item.
     auto finish_stream_list = [](std::vector<Item>& v, int32_t* wpi) {
-        std::stable_sort(v.begin(), v.end(), [](const Item& a, const Item& b) {
-            return std::min(a.kv_len, a.vis0) > std::min(b.kv_len, b.vis0);
-        });
+        sort_longest_first(v, [](const Item& it) { return std::min(it.kv_len, it.vis0); });
         int64_t total = 0;
         for (const Item& it : v) total += std::min(it.kv_len, it.vis0);
         const int64_t mean = v.empty() ? 0 : total / static_cast<int64_t>(v.size());
