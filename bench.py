@@ -30,6 +30,7 @@ MEASURED_TRAFFIC_BYTES = {
                    "single_launch": 398.4e6},
     "rank_longprefix": {"suffix": 332.2e6, "prefix": 231.8e6, "merge": 43.0e6, "suffix_merged": 341.0e6,
                         "one_call": 540.6e6, "single_launch": 540.6e6},
+    "l8b_decode_prefill": {"prefix": 393.6e6, "suffix_merged": 308.9e6, "one_call": 680.5e6, "single_launch": 754.2e6},
     "l8b_mixed": {"suffix": 852.3e6, "prefix": 692.0e6, "merge": 709.4e6, "suffix_merged": 1004.1e6, "one_call": 986.6e6,
                   "single_launch": 998.2e6},
 }
