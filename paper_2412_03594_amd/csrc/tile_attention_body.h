@@ -55,10 +55,12 @@ constexpr float kMaxSlack = 8.f;
 // gfx950-only instructions live in small device functions whose bodies exist in the device
 // pass only: the host pass cannot type-check these builtins, and a kernel template whose body
 // fails there silently loses its launch stub.
+template <bool kStreaming = false>
 __device__ __forceinline__ void dma16_to_lds(const unsigned char* gptr, unsigned char* lds_wave_base) {
 #if defined(__HIP_DEVICE_COMPILE__)
-    // every lane moves 16 bytes from its own global address to lds_wave_base + 16 * lane
-    __builtin_amdgcn_global_load_lds(gptr, (lds_void_ptr)lds_wave_base, 16, 0, 0);
+    // every lane moves 16 bytes from its own global address to lds_wave_base + 16 * lane; kStreaming marks the
+    // data as read once (non-temporal), so that it does not push reused K/V of other tiles out of the L2
+    __builtin_amdgcn_global_load_lds(gptr, (lds_void_ptr)lds_wave_base, 16, 0, kStreaming ? 2 : 0);
 #endif
 }
 
@@ -242,6 +244,21 @@ __device__ __forceinline__ void tile_attention_body(
             dma16_to_lds(vt + (rc * row_bytes + (v_unit(lane & 15, r) << 4)), lds_v);
         }
     };
+    // The same for a wavefront without rows (see idle_step): its tile belongs to a group of few rows, whose K/V
+    // no other workgroup of the compute die reads, so its loads are marked as streaming.
+    auto dma_tile_streaming = [&](int tile, unsigned char* dst_buf) {
+        const unsigned char* kt = kg + tile * tile_stride;
+        const unsigned char* vt = vg + tile * tile_stride;
+        const int rows_left = kv_len - tile * kBN;
+#pragma unroll
+        for (int jj = 0; jj < kInstrPerWave; ++jj) {
+            const int r = 4 * (wave * kInstrPerWave + jj) + (lane >> 4);
+            const int rc = min(r, rows_left - 1);
+            unsigned char* lds_k = dst_buf + (wave * kInstrPerWave + jj) * 1024;
+            dma16_to_lds<true>(kt + (rc * row_bytes + (k_unit(lane & 15, r) << 4)), lds_k);
+            dma16_to_lds<true>(vt + (rc * row_bytes + (v_unit(lane & 15, r) << 4)), lds_k + kTileBytes);
+        }
+    };
     auto dma_tile = [&](int tile, unsigned char* dst_buf) {
         const bool full = kv_len - tile * kBN >= kBN;
 #pragma unroll
@@ -388,7 +405,7 @@ __device__ __forceinline__ void tile_attention_body(
     // tile and keeps the barriers: the workgroup then steps as fast as its busy wavefronts.  It has a loop of
     // its own, so that the step of the busy wavefronts stays the straight-line code it was.
     auto idle_step = [&](int tile, unsigned char* sb_next) {
-        if (tile + 1 < n_tiles) dma_tile(tile + 1, sb_next);
+        if (tile + 1 < n_tiles) dma_tile_streaming(tile + 1, sb_next);
         wait_vector_memory<0>();
         __syncthreads();
     };
