@@ -353,3 +353,27 @@ def test_through_threshold_tuning_hook(monkeypatch):
     assert n_pairs() == 0
     monkeypatch.setenv("BLLM_TUNE_THROUGH_GAIN", "1000000")
     assert n_pairs() == 4 + 4                   # and the 34-row chunk
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_prefix_tiles_order_longest_first_with_prefix_rows_spread(seed):
+    """Order of the shared-prefix tile list: the tiles of prefix rows and the tiles of request rows each run longest KV
+    range first, and the former are spread evenly among the latter (in any leading part of the list their share is
+    within one tile of their share of the whole list)."""
+    b = workload.ragged_toy(seed, dtype=workload.BF16, n_q_heads=8, n_kv_heads=2, head_dim=128, n_groups=5,
+                            max_prefix=900, max_group=6, max_suffix=200, max_chunk=60)
+    b = workload.with_prefix_prefill(b, seed=seed)
+    m = host_pack(b).metadata()
+    first_prefix_row = m["group_prefix_row_start"][0]
+    for name in ("prefix_tile_items", "through_prefix_tile_items"):
+        items = m[name]
+        if len(items) == 0:
+            continue
+        is_pre = items[:, 0] >= first_prefix_row
+        for kind in (items[is_pre], items[~is_pre]):
+            assert np.all(np.diff(kind[:, 4]) <= 0), name
+        n_pre, total = int(is_pre.sum()), len(items)
+        if 0 < n_pre < total:
+            seen = np.cumsum(is_pre)
+            k = np.arange(1, total + 1)
+            assert np.all(np.abs(seen * total - k * n_pre) <= total), name
