@@ -546,3 +546,19 @@ def test_library_loaded_before_torch_in_a_fresh_process():
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     r = subprocess.run([sys.executable, "-c", code], cwd=root, capture_output=True, text=True, timeout=180)
     assert r.returncode == 0 and r.stdout.strip().endswith("ok"), (r.stdout, r.stderr)
+
+
+@pytest.mark.parametrize("prefix", [100, 0])
+def test_batch_of_nothing_but_chunks_that_go_through(prefix):
+    """Every row of the batch belongs to a chunk that one workgroup takes through both parts: the one-call entry
+    point then has a single launch of pairs to make and nothing else (no other prefix tile, no suffix kernel)."""
+    import paper_2412_03594_amd as bllm
+    L = workload.Layer(8, 2, 128, workload.BF16)
+    b = workload.Batch("all_through", L, np.array([prefix, prefix], np.int32), np.array([0, 1, 1], np.int32),
+                       np.array([64, 96, 40], np.int32), np.array([64, 32, 32], np.int32))
+    pg = bllm.prefix_group_create(layer_tuple(L), b.prefix_len, b.req_group, b.req_suffix_len, b.req_q_len, host_only=True)
+    m = pg.metadata()
+    assert len(m["through_pair_items"]) == 4 * 2 and len(m["through_prefix_tile_items"]) == 0
+    assert len(m["through_suffix_tile_items"]) == 0 and len(m["suffix_row_items"]) == 0
+    pg.destroy()
+    check_all(b, workload.draw_values(b))
