@@ -562,3 +562,20 @@ def test_batch_of_nothing_but_chunks_that_go_through(prefix):
     assert len(m["through_suffix_tile_items"]) == 0 and len(m["suffix_row_items"]) == 0
     pg.destroy()
     check_all(b, workload.draw_values(b))
+
+
+@pytest.mark.parametrize("seed", range(300, 320))
+def test_random_chunk_batches_all_forms(seed):
+    """Seeded random batches with larger prefill chunks (so that some go through both parts in one workgroup and some
+    do not) over head ratios 1 to 8 and prefixes from empty to 1500 tokens, every third with prefix-prefill rows:
+    every call form against the oracle."""
+    combos = [(8, 2), (8, 1), (4, 4), (16, 8), (32, 8), (64, 8), (16, 4)]
+    hq, hkv = combos[seed % len(combos)]
+    rng = np.random.default_rng(seed)
+    b = workload.ragged_toy(seed, dtype=workload.BF16, n_q_heads=hq, n_kv_heads=hkv, head_dim=128,
+                            n_groups=int(rng.integers(1, 5)), max_prefix=int(rng.choice([0, 70, 500, 1500])) or 1,
+                            max_group=int(rng.integers(1, 7)), max_suffix=int(rng.choice([100, 400, 900])),
+                            max_chunk=int(rng.choice([40, 130, 400])))
+    if seed % 3 == 0:
+        b = workload.with_prefix_prefill(b, seed=seed, max_rows=int(rng.choice([50, 400])) if seed % 2 else None)
+    check_all(b, workload.draw_values(b), append=(seed % 2 == 0))
