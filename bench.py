@@ -311,11 +311,50 @@ def machine_attainable(torch):
             "note": "1 GiB device-to-device copy, bytes read + written"}
 
 
-def host_steps(batch, bllm, with_oracle=True):
+def prefix_identification_input():
+    """The paper's grouping-ablation input (Sec. 4.4.1, setting A): 50 groups x 64 subcategories x 2 prompts of 1000
+    tokens (490-token group prefix + 11-token subcategory prefix), as a list of token arrays."""
+    rng = np.random.default_rng(0)
+    rows = []
+    for _ in range(50):
+        gp = rng.integers(0, 1 << 30, 490)
+        for _ in range(64):
+            sp = rng.integers(0, 1 << 30, 11)
+            rows += [np.concatenate([gp, sp, rng.integers(0, 1 << 30, 499)]) for _ in range(2)]
+    return rows
+
+
+def token_batching_input():
+    rng = np.random.default_rng(1)
+    n_groups = 1000
+    prefix_len = rng.integers(1200, 1900, n_groups)
+    req_group = np.repeat(np.arange(n_groups), 3)
+    distinct = rng.integers(10, 60, req_group.shape[0])
+    decode = rng.integers(96, 160, req_group.shape[0])
+    return prefix_len, req_group, distinct, decode
+
+
+def oracle_host_baselines():
+    """The CPU references of the two host steps timed on bounded samples of the inputs of host_steps (part of the
+    CPU-baseline leg: the only place besides oracle_baseline where bench.py runs anything of oracle/)."""
+    from oracle import prefix_groups, token_batching
+    rows = prefix_identification_input()
+    sample = [r.tolist() for r in rows[:5 * 128]]
+    t0 = time.perf_counter()
+    prefix_groups.identify_prefix_groups(sample)
+    t_ident = time.perf_counter() - t0
+    prefix_len, req_group, distinct, decode = token_batching_input()
+    t0 = time.perf_counter()
+    token_batching.run_job(prefix_len[:100], req_group[:300], distinct[:300], decode[:300], 2048, 400000)
+    t_batch = time.perf_counter() - t0
+    return {"prefix_identification_ms_on_640_prompts": round(t_ident * 1e3, 1),
+            "token_batching_ms_on_300_requests": round(t_batch * 1e3, 1)}
+
+
+def host_steps(batch, bllm):
     """Host-side integer steps, in wall-clock time (no roofline applies): the token-batch packing of
     the bench workload, and the global prefix identification on the paper's grouping-ablation input
-    (Sec. 4.4.1, setting A: 50 groups x 64 subcategories x 2 prompts of 1000 tokens), with the Python
-    reference timed beside it on 5 of the 50 groups."""
+    (Sec. 4.4.1, setting A: 50 groups x 64 subcategories x 2 prompts of 1000 tokens)."""
     L = batch.layer
     best = float("inf")
     for _ in range(5):
@@ -324,13 +363,7 @@ def host_steps(batch, bllm, with_oracle=True):
                                       batch.req_suffix_len, batch.req_q_len, host_only=True)
         best = min(best, time.perf_counter() - t0)
         pg.destroy()
-    rng = np.random.default_rng(0)
-    rows = []
-    for _ in range(50):
-        gp = rng.integers(0, 1 << 30, 490)
-        for _ in range(64):
-            sp = rng.integers(0, 1 << 30, 11)
-            rows += [np.concatenate([gp, sp, rng.integers(0, 1 << 30, 499)]) for _ in range(2)]
+    rows = prefix_identification_input()
     flat = np.concatenate(rows).astype(np.int32)
     start = np.arange(len(rows) + 1, dtype=np.int64) * 1000
     t0 = time.perf_counter()
@@ -340,29 +373,17 @@ def host_steps(batch, bllm, with_oracle=True):
            "prefix_identification": {"input": "6400 prompts x 1000 tokens, 490-token group prefix + 11-token sub prefix",
                                      "ms": round(t_ident * 1e3, 2), "groups": int(len(prefix_len)),
                                      "saving_ratio_percent": round(100.0 * (1.0 - processed / logical), 1)}}
-    if with_oracle:
-        from oracle import prefix_groups as ref
-        sample = [r.tolist() for r in rows[:5 * 128]]
-        t0 = time.perf_counter()
-        ref.identify_prefix_groups(sample)
-        out["prefix_identification"]["oracle_ms_on_640_prompts"] = round((time.perf_counter() - t0) * 1e3, 1)
-    out["token_batching"] = token_batching_job(bllm, with_oracle)
+    out["token_batching"] = token_batching_job(bllm)
     return out
 
 
-def token_batching_job(bllm, with_oracle):
+def token_batching_job(bllm):
     """The token batches of a whole synthetic job shaped like the paper's offline workloads (Sec. 4.2:
     3000 requests, sharing degree about 3, prefix about 1.5k tokens, distinct part about 30, outputs in a
     narrow range; Sec. 3.3.3: S_chunk tokens per batch): tokens per iteration with the paper's batching
     (groups reordered by Eq. 3, limited by the KV memory) and with a request-count limit of 256 in arrival
     order, the setting the paper contrasts it with."""
-    rng = np.random.default_rng(1)
-    n_groups = 1000
-    prefix_len = rng.integers(1200, 1900, n_groups)
-    req_group = np.repeat(np.arange(n_groups), 3)
-    distinct = rng.integers(10, 60, req_group.shape[0])
-    decode = rng.integers(96, 160, req_group.shape[0])
-    job = (prefix_len, req_group, distinct, decode)
+    job = token_batching_input()
     out = {"input": "1000 groups x 3 requests, prefix U[1200,1900), distinct U[10,60), output U[96,160); "
                     "S_chunk 2048, M_threshold 400000 KV tokens"}
     for name, kw in (("memory_centric_reordered", {}), ("request_limit_256_arrival_order", {"max_requests": 256, "reorder": False})):
@@ -371,12 +392,6 @@ def token_batching_job(bllm, with_oracle):
         dt = time.perf_counter() - t0
         out[name] = {"ms": round(dt * 1e3, 2), "iterations": int(len(tokens)), "mean_tokens_per_iteration": round(float(tokens.mean()), 1),
                      "iterations_below_half_chunk": int((tokens < 1024).sum()), "peak_kv_tokens": int(kv.max())}
-    if with_oracle:
-        from oracle import token_batching as ref
-        sub = (prefix_len[:100], req_group[:300], distinct[:300], decode[:300])
-        t0 = time.perf_counter()
-        ref.run_job(*sub, 2048, 400000)
-        out["oracle_ms_on_300_requests"] = round((time.perf_counter() - t0) * 1e3, 1)
     return out
 
 
@@ -566,9 +581,10 @@ def main():
         "passes": main_res["passes"],
     }
     out["machine"] = machine_attainable(torch)
-    out["host_steps"] = host_steps(batch, bllm, with_oracle=not args.no_cpu_baseline)
+    out["host_steps"] = host_steps(batch, bllm)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = oracle_baseline(batch, main_res["vals"])
+        out["cpu_baseline"]["host_steps"] = oracle_host_baselines()
     others = {}
     for name in [n for n in args.also.split(",") if n and n != args.workload]:
         # values drawn on the device: the other workloads are only timed, nothing reads their values on the host
